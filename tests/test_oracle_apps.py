@@ -1,0 +1,192 @@
+"""Pins for the oracle's application definitions (CPU only): closed forms,
+library routines that compute the same thing by other means (numpy fancy
+indexing / bincount / fsum, scipy's graph search), special cases, and
+invariants of the result."""
+import math
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+from scipy.sparse.csgraph import shortest_path
+
+import oracle
+from paper_2411_05309_amd import inputs
+
+
+# ---------------------------------------------------------------- gather
+
+def test_gather_closed_form_and_library():
+    n = 1000
+    host = np.arange(n, dtype=np.uint32) * 3 + 1
+    idx = np.array([0, 999, 5, 5, 17, 0], np.uint32)
+    out, s = oracle.gather(host, idx)
+    assert out.tolist() == [1, 2998, 16, 16, 52, 1]
+    assert s == 1 + 2998 + 16 + 16 + 52 + 1
+    rng = np.random.default_rng(0)
+    host = rng.integers(0, 1 << 32, 5000, dtype=np.uint64).astype(np.uint32)
+    idx = rng.integers(0, 5000, 20000).astype(np.uint32)
+    out, s = oracle.gather(host, idx)
+    assert np.array_equal(out, host[idx])
+    assert s == sum(int(v) for v in host[idx])
+
+
+def test_gather_sum_needs_64_bits_and_empty():
+    host = np.full(4, 0xFFFFFFFF, np.uint32)
+    out, s = oracle.gather(host, np.zeros(10, np.uint32))
+    assert s == 10 * 0xFFFFFFFF                       # > 2^32
+    out, s = oracle.gather(host, np.zeros(0, np.uint32))
+    assert out.size == 0 and s == 0
+
+
+# ---------------------------------------------------------------- stream
+
+def test_stream_reduce_closed_forms():
+    # x[i] = i / 2^10, i < 2^12: exact in fp32; block sums are arithmetic series
+    n, blk = 4096, 1000
+    x = (np.arange(n) / 1024.0).astype(np.float32)
+    s = oracle.stream_reduce(x, blk, 3)
+    assert s.shape == (3, 5)
+    for b in range(5):
+        lo, hi = b * blk, min(n, (b + 1) * blk)
+        assert s[0, b] == (hi * (hi - 1) // 2 - lo * (lo - 1) // 2) / 1024.0
+    assert np.array_equal(s[0], s[1]) and np.array_equal(s[0], s[2])
+
+
+def test_stream_reduce_against_exact_summation():
+    x = inputs.f32_uniform(7, 0, 10000)
+    assert x.min() >= -1.0 and x.max() < 1.0
+    s = oracle.stream_reduce(x, 1024, 1)[0]
+    a = oracle.stream_abs(x, 1024)
+    for b in range(10):
+        blk = x[b * 1024:(b + 1) * 1024].astype(np.float64)
+        assert abs(s[b] - math.fsum(blk)) <= 1e-12 * math.fsum(np.abs(blk))
+        assert abs(a[b] - math.fsum(np.abs(blk))) <= 1e-12 * a[b]
+    # sign symmetry: a dropped or doubled element would break one of these
+    assert np.allclose(oracle.stream_reduce(-x, 1024, 1)[0], -s, rtol=0, atol=0)
+
+
+# ---------------------------------------------------------------- BFS
+
+def _csr(nv, edges):
+    src = np.array([e[0] for e in edges], np.int64)
+    dst = np.array([e[1] for e in edges], np.int64)
+    order = np.argsort(src, kind="stable")
+    row_ptr = np.zeros(nv + 1, np.int64)
+    np.cumsum(np.bincount(src, minlength=nv), out=row_ptr[1:])
+    return row_ptr, dst[order].astype(np.int32)
+
+
+def test_bfs_special_graphs():
+    n = 50
+    rp, ci = _csr(n, [(i, i + 1) for i in range(n - 1)])           # directed path
+    assert oracle.bfs(rp, ci, 0).tolist() == list(range(n))
+    assert oracle.bfs(rp, ci, 10).tolist() == [-1] * 10 + list(range(n - 10))
+    rp, ci = _csr(n, [(0, i) for i in range(1, n)])                 # star
+    assert oracle.bfs(rp, ci, 0).tolist() == [0] + [1] * (n - 1)
+    assert oracle.bfs(rp, ci, 3).tolist() == [-1] * 3 + [0] + [-1] * (n - 4)
+    rp, ci = _csr(63, [(v, 2 * v + 1) for v in range(31)] + [(v, 2 * v + 2) for v in range(31)])
+    assert oracle.bfs(rp, ci, 0).tolist() == [int(math.log2(v + 1)) for v in range(63)]
+    rp, ci = _csr(4, [(0, 0), (0, 1), (0, 1), (1, 0), (2, 3)])      # loops, duplicates
+    assert oracle.bfs(rp, ci, 0).tolist() == [0, 1, -1, -1]
+
+
+def test_bfs_against_scipy_on_rmat():
+    scale = 10
+    rp, ci = inputs.rmat_csr(3, scale, edge_factor=8)
+    nv = 1 << scale
+    assert rp[-1] == ci.size == 8 << scale
+    level = oracle.bfs(rp, ci, 0)
+    m = sp.csr_matrix((np.ones(ci.size, np.int8), ci.copy(), rp.copy()), shape=(nv, nv))
+    m.sum_duplicates()
+    d = shortest_path(m, method="D", directed=True, unweighted=True, indices=0)
+    want = np.where(np.isinf(d), -1, d).astype(np.int32)
+    assert np.array_equal(level, want)
+    # structural invariants of any BFS labelling
+    assert level[0] == 0
+    src = np.repeat(np.arange(nv), np.diff(rp))
+    reach = level[src] >= 0
+    assert np.all(level[ci[reach]] >= 0)
+    assert np.all(level[ci[reach]] <= level[src[reach]] + 1)
+    has_parent = np.zeros(nv, bool)
+    par = reach & (level[ci] == level[src] + 1)
+    has_parent[ci[par]] = True
+    assert np.all(has_parent[level > 0])
+
+
+# ---------------------------------------------------------------- embedding bag
+
+def test_embedding_bag_closed_form():
+    rows, dim = 100, 8
+    table = (np.arange(rows)[:, None] * np.ones(dim)[None, :]).astype(np.float32)
+    table += np.arange(dim, dtype=np.float32)[None, :] * 1000
+    ids = np.array([[1, 2, 3, 4], [7, 7, 7, 7], [99, 0, 0, 99]], np.int32)
+    want = ids.sum(1)[:, None] + 4000.0 * np.arange(dim)[None, :]
+    assert np.array_equal(oracle.embedding_bag(table, ids), want)
+    assert np.array_equal(oracle.embedding_bag_f32(table, ids), want.astype(np.float32))
+    assert np.array_equal(oracle.embedding_bag_abs(table, ids), want)
+
+
+def test_embedding_bag_against_numpy_and_ordered_fp32():
+    rng = np.random.default_rng(4)
+    table = inputs.f32_uniform(11, 0, 300 * 16).reshape(300, 16)
+    ids = inputs.bag_row_ids(5, 0, 50 * 32, 300, scramble=False).reshape(50, 32)
+    assert ids.min() >= 0 and ids.max() < 300
+    ref = table.astype(np.float64)[ids].sum(axis=1)
+    got = oracle.embedding_bag(table, ids)
+    assert np.max(np.abs(got - ref)) <= 1e-13 * 32
+    # fp32 variant: one rounding per addition, rows in listed order
+    f32 = oracle.embedding_bag_f32(table, ids)
+    acc = np.zeros((50, 16), np.float32)
+    for j in range(32):
+        acc = (acc + table[ids[:, j]]).astype(np.float32)
+    assert np.array_equal(f32, acc)
+    scale = oracle.embedding_bag_abs(table, ids)
+    assert np.all(np.abs(f32 - ref) <= 1e-5 * scale)
+    # order matters in fp32, not in the definition: reversed bags
+    assert np.allclose(oracle.embedding_bag(table, ids[:, ::-1].copy()), got, rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- scatter
+
+def test_scatter_increment_is_a_histogram():
+    idx = inputs.scatter_indices(3, 0, 100000, 1 << 12)
+    assert idx.max() < 1 << 12
+    host = np.zeros(1 << 12, np.uint64)
+    oracle.scatter_increment(host, idx)
+    assert np.array_equal(host, np.bincount(idx, minlength=1 << 12).astype(np.uint64))
+    assert int(host.sum()) == 100000
+    oracle.scatter_increment(host, idx[:10])                     # accumulates
+    assert int(host.sum()) == 100010
+
+
+# ---------------------------------------------------------------- input generators
+
+def test_generators_are_counter_based_and_shaped():
+    a = inputs.u32_values(1, 0, 1000)
+    b = np.concatenate([inputs.u32_values(1, 0, 300), inputs.u32_values(1, 300, 700)])
+    assert np.array_equal(a, b) and len(set(a.tolist())) > 990
+    i = inputs.u32_indices(2, 0, 100000, 1 << 24)
+    assert i.max() < 1 << 24 and abs(i.mean() / (1 << 23) - 1) < 0.02
+    x = inputs.f32_uniform(3, 0, 200000)
+    assert abs(x.mean()) < 0.01 and abs(x.var() - 1 / 3) < 0.01
+    r = inputs.zipf_ranks(4, 0, 200000, 10 ** 6, 1.05)
+    assert r.min() >= 1 and r.max() <= 10 ** 6
+    assert np.mean(r <= 10) > 0.2                              # heavy head
+    ids = inputs.bag_row_ids(4, 0, 1000, 5 * 10 ** 7)
+    assert ids.min() >= 0 and ids.max() < 5 * 10 ** 7
+    rp, ci = inputs.rmat_csr(1, 8)
+    deg = np.diff(rp)
+    assert deg.argmax() == 0 and deg.max() > 20 * deg.mean()   # vertex 0 is the hub
+
+
+def test_torch_twins_match_numpy():
+    import torch
+    assert np.array_equal(inputs.t_u32_values(5, 100, 999, "cpu").numpy().view(np.uint32),
+                          inputs.u32_values(5, 100, 999))
+    assert np.array_equal(inputs.t_u32_indices(6, 7, 999, 1 << 24, "cpu").numpy().view(np.uint32),
+                          inputs.u32_indices(6, 7, 999, 1 << 24))
+    assert np.array_equal(inputs.t_f32_uniform(7, 50, 999, "cpu").numpy(),
+                          inputs.f32_uniform(7, 50, 999))
+    rp, ci = inputs.rmat_csr(2, 9)
+    trp, tci = inputs.t_rmat_csr(2, 9, "cpu", chunk=1000)
+    assert np.array_equal(trp.numpy(), rp) and np.array_equal(tci.numpy(), ci)

@@ -1,0 +1,366 @@
+"""Pins for the oracle's paged-memory simulator (CPU only).
+
+What fixes the expected values here is never the simulator itself:
+  * textbook FIFO fault counts (Belady's anomaly string; the 20-reference
+    string of the standard OS textbook),
+  * closed forms (compulsory misses only; cyclic scan),
+  * two independently written models from the textbook descriptions of the
+    policies -- FIFO as a bounded queue, second chance as a queue whose head is
+    re-appended with its bit cleared -- compared on exhaustive tiny traces,
+  * traces worked by hand from the stated reading (derivations below),
+  * invariants checked after every phase of random runs, and the data that
+    must survive eviction + write-back + flush.
+"""
+import itertools
+import os
+from collections import deque
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import ADD, CLOCK, FIFO, READ, WRITE, PagingSim
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _gold(name):
+    rows = []
+    with open(os.path.join(GOLD, name)) as fh:
+        for line in fh:
+            line = line.split("#")[0].split()
+            if line:
+                rows.append(line)
+    return rows
+
+
+def _run_pages(pages, frames, policy, writes=None, phase_len=1, n_pages=None):
+    """Page-granular trace through the simulator (one word per page)."""
+    n_pages = n_pages or (max(pages) + 1)
+    sim = PagingSim(1, frames, policy, n_words=n_pages)
+    op = None if writes is None else np.where(np.asarray(writes), WRITE, READ).astype(np.uint8)
+    sim.run(np.asarray(pages, np.uint64), op=op, phase_len=phase_len)
+    return sim
+
+
+# ---------------------------------------------------------------- textbook
+
+def test_belady_anomaly_fifo():
+    rows = _gold("belady_fifo.txt")
+    refs = [int(x) for x in rows[0][1:]]
+    for row in rows[1:]:
+        frames, faults, owner = int(row[1]), int(row[2]), [int(x) for x in row[3:]]
+        sim = _run_pages(refs, frames, FIFO)
+        assert sim.counters["faults"] == faults
+        assert sim.counters["hits"] == len(refs) - faults
+        assert sim.state()["owner"].tolist() == owner
+        # every reference bit is set when the hand arrives, so CLOCK walks one
+        # full turn and takes the same victim: same faults, same placement
+        simc = _run_pages(refs, frames, CLOCK)
+        assert simc.counters["faults"] == faults
+        assert simc.state()["owner"].tolist() == owner
+
+
+def test_os_textbook_string_fifo():
+    rows = _gold("os_textbook_fifo.txt")
+    refs = [int(x) for x in rows[0][1:]]
+    frames, faults = int(rows[1][1]), int(rows[1][2])
+    assert _run_pages(refs, frames, FIFO).counters["faults"] == faults
+
+
+# ---------------------------------------------------------------- closed forms
+
+@pytest.mark.parametrize("policy", [FIFO, CLOCK])
+def test_compulsory_misses_only(policy):
+    rng = np.random.default_rng(5)
+    pages = rng.integers(0, 40, 2000)
+    sim = _run_pages(pages.tolist(), 40, policy, n_pages=40)
+    c = sim.counters
+    assert c["faults"] == len(set(pages.tolist()))
+    assert c["evictions"] == 0 and c["writebacks_evict"] == 0
+    assert c["hits"] == len(pages) - c["faults"]
+    # frames are handed out in ring order: the i-th new page sits in frame i
+    first = list(dict.fromkeys(pages.tolist()))
+    assert sim.state()["owner"][:len(first)].tolist() == first
+
+
+@pytest.mark.parametrize("policy", [FIFO, CLOCK])
+@pytest.mark.parametrize("n,f,t", [(10, 3, 4), (17, 16, 3), (64, 16, 3), (5, 1, 2)])
+def test_cyclic_scan(policy, n, f, t):
+    """N pages scanned T times with F < N frames: every access faults."""
+    sim = _run_pages(list(range(n)) * t, f, policy)
+    c = sim.counters
+    assert c["faults"] == t * n and c["hits"] == 0
+    assert c["evictions"] == t * n - f
+    assert c["writebacks_evict"] == 0 and c["skips"] == 0
+
+
+def test_streaming_config_closed_form():
+    """The streaming workload: 8 GiB in 64 KiB pages, 2 GiB pool, 3 passes."""
+    n, f, t = 131072, 32768, 3
+    sim = PagingSim(1, f, CLOCK, n_words=n)
+    sim.run(np.tile(np.arange(n, dtype=np.uint64), t))
+    c = sim.counters
+    assert c["faults"] == 393216 and c["evictions"] == 360448
+    assert c["faults"] * 65536 == 24 << 30
+
+
+# ---------------------------------------------------------------- independent models
+
+def fifo_queue_model(refs, frames):
+    """FIFO as every textbook states it: a queue of resident pages."""
+    q, faults = deque(), 0
+    for p in refs:
+        if p in q:
+            continue
+        faults += 1
+        if len(q) == frames:
+            q.popleft()
+        q.append(p)
+    return faults, set(q)
+
+
+def second_chance_queue_model(refs, frames):
+    """Second chance as a FIFO queue: the oldest page is inspected; if its R
+    bit is set it is cleared and the page goes to the back as if it had just
+    arrived; otherwise it is evicted.  R is set on load and on every use."""
+    q, rbit, faults = deque(), {}, 0
+    for p in refs:
+        if p in rbit:
+            rbit[p] = 1
+            continue
+        faults += 1
+        if len(q) == frames:
+            while True:
+                old = q.popleft()
+                if rbit[old]:
+                    rbit[old] = 0
+                    q.append(old)
+                else:
+                    del rbit[old]
+                    break
+        q.append(p)
+        rbit[p] = 1
+    return faults, set(q)
+
+
+def test_exhaustive_small_traces_against_queue_models():
+    checked = 0
+    for npages, frames, length in [(3, 2, 6), (4, 2, 6), (4, 3, 7), (5, 3, 6)]:
+        for refs in itertools.product(range(npages), repeat=length):
+            f_faults, f_set = fifo_queue_model(refs, frames)
+            c_faults, c_set = second_chance_queue_model(refs, frames)
+            sf = _run_pages(list(refs), frames, FIFO, n_pages=npages)
+            sc = _run_pages(list(refs), frames, CLOCK, n_pages=npages)
+            assert sf.counters["faults"] == f_faults, refs
+            assert sc.counters["faults"] == c_faults, refs
+            assert set(sf.state()["owner"][sf.state()["owner"] >= 0].tolist()) == f_set
+            assert set(sc.state()["owner"][sc.state()["owner"] >= 0].tolist()) == c_set
+            checked += 1
+    assert checked > 20000
+
+
+def test_random_long_traces_against_queue_models():
+    rng = np.random.default_rng(11)
+    for _ in range(40):
+        npages = int(rng.integers(4, 60))
+        frames = int(rng.integers(1, npages))
+        # skewed references so that CLOCK and FIFO really differ
+        refs = np.minimum(rng.geometric(0.15, 3000) - 1, npages - 1).tolist()
+        ff, fs = fifo_queue_model(refs, frames)
+        cf, cs = second_chance_queue_model(refs, frames)
+        sf = _run_pages(refs, frames, FIFO, n_pages=npages)
+        sc = _run_pages(refs, frames, CLOCK, n_pages=npages)
+        assert sf.counters["faults"] == ff and sc.counters["faults"] == cf
+        own = sc.state()["owner"]
+        assert set(own[own >= 0].tolist()) == cs
+        own = sf.state()["owner"]
+        assert set(own[own >= 0].tolist()) == fs
+
+
+def test_clock_keeps_a_reused_page_that_fifo_drops():
+    # 3 frames.  1 2 3 fill; 4 turns the hand once (clearing all bits) and
+    # replaces 1.  Then 2 is used again (bit set), 5 must replace 3 (bit clear
+    # at the hand), not 2; FIFO replaces 2 (the oldest).  6th reference to 2:
+    # hit under CLOCK, fault under FIFO.
+    refs = [1, 2, 3, 4, 2, 5, 2]
+    assert _run_pages(refs, 3, FIFO).counters["faults"] == 6
+    assert _run_pages(refs, 3, CLOCK).counters["faults"] == 5
+
+
+# ---------------------------------------------------------------- hand-worked traces
+
+def _parse_expect(row):
+    d, i = {}, 1
+    while row[i] != "owner":
+        d[row[i]] = int(row[i + 1])
+        i += 2
+    d["owner"] = [int(x) for x in row[i + 1:]]
+    return d
+
+
+def _check_expect(sim, exp):
+    sim.flush()
+    c = sim.counters
+    for k, v in exp.items():
+        if k == "owner":
+            assert sim.state()["owner"].tolist() == v
+        else:
+            assert c[k] == v, (k, c)
+
+
+def test_hand_trace_dirty_f3():
+    """3 frames, phase length 1: 1R 2W 3R 1R 4R 1R 5R 2R 1W 3R.
+
+    FIFO: 1,2,3 fill frames 0,1,2 (2 dirty).  1R hits.  4 takes frame 0
+    (drops 1, clean).  1 faults again, takes frame 1 (page 2 is dirty: first
+    write-back).  5 takes frame 2 (drops 3).  2 takes frame 0 (drops 4).  1W
+    hits in frame 1 and dirties it.  3 takes frame 1 (page 1 dirty: second
+    write-back).  8 faults, 2 hits, 5 evictions, 2 write-backs, frames hold
+    2,3,5, nothing dirty is left for the flush.
+
+    CLOCK: after the fill all bits are set; 1R changes nothing.  4 clears the
+    bits of frames 0,1,2 (3 sweeps) and takes frame 0.  1 takes frame 1 (bit
+    clear; page 2 dirty: write-back).  5 takes frame 2.  2: hand at 0, bits of
+    0,1,2 are set (installed since): 3 more sweeps, takes frame 0.  1W hits in
+    frame 1, sets its bit, dirties it.  3: hand at 1, bit set -> cleared (7th
+    sweep), frame 2 has a clear bit: drops 5.  Frames hold 2,1,3; page 1 is
+    still dirty: one flush write-back.
+    """
+    rows = _gold("trace_dirty_f3.txt")
+    acc = rows[0][1:]
+    pages = [int(a[:-1]) for a in acc]
+    writes = [a[-1] == "W" for a in acc]
+    for row, pol in ((rows[1], FIFO), (rows[2], CLOCK)):
+        _check_expect(_run_pages(pages, 3, pol, writes), _parse_expect(row))
+
+
+def test_hand_trace_phased_f4():
+    """4 frames, three phases of four accesses (derivation: the distinct pages
+    of a phase are pinned while it lasts; hits are pinned first, faults are
+    served in ascending page order; a pinned frame is passed over).
+
+    Phase 1 {0,1,2}: frames 0,1,2; hand 3; page 1 dirty.
+    Phase 2 {1,3,4,5}: 1 hits (pinned).  3 takes the empty frame 3.  4: FIFO
+    takes frame 0 (drops 0); CLOCK first clears frame 0, passes pinned 1,
+    clears 2, passes pinned 3, then takes frame 0.  5: frame 1 is pinned,
+    frame 2 (page 2) is taken.  4 is dirty.  Frames 4,1,5,3, hand 3.
+    Phase 3 {0,1,4,6}: 1 and 4 hit.  0: FIFO takes frame 3 (drops 3); CLOCK
+    clears 3, passes pinned 0 and 1, clears 2, takes frame 3.  6: passes
+    pinned 0 and 1, takes frame 2 (drops 5).  0 is dirty.
+    Totals: 8 faults, 3 hits, 4 evictions, no eviction write-back (victims
+    0,2,3,5 were clean), flush writes 1, 4 and 0.  Passed-over pinned frames:
+    FIFO 1+2 = 3, CLOCK 3+4 = 7; CLOCK bit clearings 2+2 = 4.
+    """
+    rows = _gold("trace_phased_f4.txt")
+    phases = [r[1:] for r in rows if r[0] == "phase"]
+    for row in rows:
+        if row[0] not in ("fifo", "clock"):
+            continue
+        sim = PagingSim(1, 4, FIFO if row[0] == "fifo" else CLOCK, n_words=7)
+        for ph in phases:
+            pages = np.array([int(a[:-1]) for a in ph], np.uint64)
+            op = np.array([WRITE if a[-1] == "W" else READ for a in ph], np.uint8)
+            sim.phase(pages, op)
+        _check_expect(sim, _parse_expect(row))
+
+
+# ---------------------------------------------------------------- invariants + data
+
+def _check_invariants(sim, n_frames):
+    st, c = sim.state(), sim.counters
+    owner, where = st["owner"], st["where"]
+    res = np.nonzero(where >= 0)[0]
+    assert len(res) <= n_frames
+    assert len(set(where[res].tolist())) == len(res)          # one frame per page
+    assert np.all(owner[where[res]] == res)                   # and back
+    assert np.count_nonzero(owner >= 0) == len(res)
+    assert np.all(st["pin"] == 0)
+    assert c["faults"] - c["evictions"] == len(res)
+    assert np.all(st["dirty"][owner < 0] == 0)
+
+
+@pytest.mark.parametrize("policy", [FIFO, CLOCK])
+def test_random_phases_invariants_and_data(policy):
+    rng = np.random.default_rng(3 + policy)
+    for trial in range(25):
+        page_words = int(rng.choice([1, 4, 16]))
+        n_words = int(rng.integers(20, 400))
+        n_pages = -(-n_words // page_words)
+        frames = int(rng.integers(2, max(3, n_pages)))
+        phase_len = int(rng.integers(1, frames + 1))
+        host = rng.integers(0, 1 << 40, n_words).astype(np.uint64)
+        model = host.copy()                 # the same ops on plain memory
+        sim = PagingSim(page_words, frames, policy, host=host)
+        for _ in range(30):
+            k = phase_len
+            idx = rng.integers(0, n_words, k).astype(np.uint64)
+            op = rng.integers(0, 3, k).astype(np.uint8)
+            val = rng.integers(0, 1000, k).astype(np.uint64)
+            got = sim.phase(idx, op, val)
+            for i in range(k):              # plain sequential semantics
+                before = model[idx[i]]
+                if op[i] == READ:
+                    assert got[i] == before
+                elif op[i] == WRITE:
+                    model[idx[i]] = val[i]
+                else:
+                    assert got[i] == before
+                    model[idx[i]] = before + val[i]
+            _check_invariants(sim, frames)
+        sim.flush()
+        assert np.all(sim.state()["dirty"] == 0)
+        assert np.array_equal(host, model)
+
+
+def test_scatter_through_paging_equals_bincount():
+    rng = np.random.default_rng(9)
+    n_words, k = 4096, 50000
+    idx = np.minimum(rng.zipf(1.3, k) - 1, n_words - 1).astype(np.uint64)
+    for policy in (FIFO, CLOCK):
+        host = np.zeros(n_words, np.uint64)
+        sim = PagingSim(64, 8, policy, host=host)
+        sim.run(idx, op=ADD, val=1, phase_len=8)
+        c = sim.counters
+        assert c["writebacks_evict"] > 0
+        assert c["writebacks_evict"] <= c["evictions"]
+        sim.flush()
+        assert np.array_equal(host, np.bincount(idx.astype(np.int64), minlength=n_words).astype(np.uint64))
+        assert int(host.sum()) == k
+
+
+def test_readonly_trace_never_writes_back():
+    rng = np.random.default_rng(2)
+    host = rng.integers(0, 1 << 60, 1000).astype(np.uint64)
+    keep = host.copy()
+    sim = PagingSim(8, 5, CLOCK, host=host)
+    idx = rng.integers(0, 1000, 5000).astype(np.uint64)
+    got = sim.run(idx, phase_len=4)
+    assert np.array_equal(got, keep[idx.astype(np.int64)])
+    sim.flush()
+    c = sim.counters
+    assert c["writebacks_evict"] == 0 and c["writebacks_flush"] == 0
+    assert np.array_equal(host, keep)
+
+
+def test_short_last_page_and_errors():
+    host = np.arange(10, dtype=np.uint64)           # pages of 4: 4 + 4 + 2 words
+    sim = PagingSim(4, 2, FIFO, host=host)
+    sim.run(np.array([9, 0, 5, 9], np.uint64), op=np.array([ADD, READ, READ, READ], np.uint8), val=7)
+    sim.flush()
+    assert host[9] == 16 and host[:9].tolist() == list(range(9))
+    with pytest.raises(IndexError):
+        sim.phase(np.array([10], np.uint64))
+    with pytest.raises(ValueError):                 # 3 distinct pages, 2 frames
+        sim.phase(np.array([0, 4, 8], np.uint64))
+
+
+def test_pinned_frames_are_never_victims():
+    # 2 frames; phase {0,1} then phase {1,2}: page 1 is pinned by the second
+    # phase, so page 2 must replace page 0 whatever the policy.
+    for policy in (FIFO, CLOCK):
+        sim = PagingSim(1, 2, policy, n_words=3)
+        sim.phase(np.array([0, 1], np.uint64))
+        sim.phase(np.array([1, 2], np.uint64))
+        assert sorted(sim.state()["owner"].tolist()) == [1, 2]
+        assert sim.counters["hits"] == 1 and sim.counters["faults"] == 3
