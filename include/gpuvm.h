@@ -1,0 +1,245 @@
+/*
+ * gpuvm.h - host-side C ABI of libgpuvm: GPU-driven demand paging for MI355X.
+ *
+ * GPU threads, not the CPU or the OS, service page faults on a data set that
+ * lives in pinned host memory and is larger than the frame pool in HBM
+ * (paper: System Overview; Paged Memory System Design).  The paper's RDMA-NIC
+ * data mover is replaced by the faulting wavefront itself, which copies the
+ * page with wide coalesced loads/stores over the host link.
+ *
+ * Conventions for every entry point:
+ *   - returns GPUVM_OK (0) or a negative GPUVM_E* code; gpuvm_strerror() names it;
+ *   - "host pointer" = ordinary CPU-addressable memory, "device pointer" = HBM
+ *     (e.g. a torch.Tensor's data_ptr()); neither is ever a torch type;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream);
+ *     kernels are enqueued on it; calls that return results to the host
+ *     synchronise that stream before returning and say so;
+ *   - a gpuvm_t belongs to the device that was current at gpuvm_create() and
+ *     may be used by one host thread / one stream at a time.
+ */
+#ifndef GPUVM_H
+#define GPUVM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GPUVM_API __attribute__((visibility("default")))
+
+/* ---- error codes ------------------------------------------------------- */
+enum {
+    GPUVM_OK      = 0,
+    GPUVM_EINVAL  = -1,  /* bad argument (null, size, alignment, policy)        */
+    GPUVM_ENOMEM  = -2,  /* device or host allocation failed                    */
+    GPUVM_EPIN    = -3,  /* host_buf is not pinned, GPU-mapped host memory      */
+    GPUVM_EDEADLK = -4,  /* frame pool too small for the waves a launch needs,
+                            or a bounded wait inside a kernel ran out           */
+    GPUVM_EHIP    = -5,  /* a HIP runtime call failed                           */
+    GPUVM_ERANGE  = -6   /* an index / id array refers outside the data set     */
+};
+
+/* ---- eviction policy (paper: Eviction scheme; Oversubscription Analysis) */
+enum {
+    GPUVM_POLICY_FIFO  = 0, /* ring of frames + reference-counter gate (the paper's) */
+    GPUVM_POLICY_CLOCK = 1  /* same ring with a second-chance reference bit          */
+};
+
+/* ---- counters ----------------------------------------------------------
+ * Wave-aggregated, accumulated since create / gpuvm_stats_clear / gpuvm_reset. */
+typedef struct gpuvm_stats {
+    uint64_t faults;            /* pages migrated host -> frame                         */
+    uint64_t evictions;         /* resident pages dropped to make room                  */
+    uint64_t writebacks_evict;  /* dirty victims copied frame -> host                   */
+    uint64_t writebacks_flush;  /* dirty pages copied by gpuvm_flush                    */
+    uint64_t bytes_in;          /* host-link bytes read by page migration               */
+    uint64_t bytes_out;         /* host-link bytes written by write-back                */
+    uint64_t hits;              /* page groups that found their page resident           */
+    uint64_t wave_page_groups;  /* distinct (wavefront, page) groups after dedup        */
+    uint64_t lanes_coalesced;   /* lanes that rode on another lane's group              */
+    uint64_t loading_waits;     /* groups that waited for another wave's fault/eviction */
+    uint64_t alloc_skips;       /* ring positions passed over: pinned / busy frame      */
+    uint64_t alloc_sweeps;      /* CLOCK reference bits cleared by the hand             */
+    uint64_t phases;            /* barrier phases run by the deterministic launchers    */
+    uint64_t reserved[3];
+} gpuvm_stats_t;
+
+/* ---- device-side view: a POD copied by value into kernel arguments -----
+ * (paper: the gpuvm<T> array-like object handed to kernels).  Layout of the
+ * tables is described in gpuvm_device.h. */
+typedef struct gpuvm_dev {
+    unsigned long long *pte;      /* [n_pages] page-table words (device)             */
+    unsigned int       *frame_owner; /* [n_frames] page living in the frame          */
+    unsigned long long *hand;     /* [0] ring cursor, [1] first error code           */
+    unsigned long long *stats;    /* [GPUVM_STAT_SLOTS][16] sharded counters         */
+    char               *frames;   /* frame pool, n_frames * page_bytes (device)      */
+    char               *host;     /* device-visible address of host_buf              */
+    uint64_t bytes;               /* size of the data set                            */
+    uint32_t n_pages, n_frames;
+    uint32_t page_shift;          /* log2(page_bytes)                                */
+    uint32_t policy;
+    uint32_t spin_limit;          /* bound on every in-kernel wait loop              */
+    uint32_t flags;               /* GPUVM_F_*                                       */
+} gpuvm_dev_t;
+
+#define GPUVM_F_ACCESS_STATS 1u   /* also count hits / groups / coalesced lanes     */
+#define GPUVM_STAT_SLOTS 64
+
+typedef struct gpuvm gpuvm_t;     /* opaque; owned by the library */
+
+/* ---- life cycle --------------------------------------------------------- */
+
+/* Pinned, GPU-mapped host memory for a backing store (hipHostMalloc).  The
+ * caller owns it and releases it with gpuvm_host_free after gpuvm_destroy. */
+GPUVM_API int gpuvm_host_alloc(size_t bytes, void **out);
+GPUVM_API int gpuvm_host_free(void *p);
+
+/* Create a paged view of host_buf (paper: Constructing Virtual Memory - the
+ * host region is allocated and registered once, before any kernel runs, and
+ * its descriptor is copied to the GPU; the GPU pool is allocated statically).
+ *   host_buf          host pointer to pinned, GPU-mapped memory (gpuvm_host_alloc,
+ *                     hipHostMalloc, or a torch tensor with pin_memory=True);
+ *                     stays the caller's, must outlive the handle, and must not
+ *                     be touched by the CPU between the first launch and
+ *                     gpuvm_flush().  Plain malloc memory -> GPUVM_EPIN.
+ *   bytes             size of the data set; the last page may be short.
+ *   page_bytes        power of two, 4 KiB .. 1 MiB; every element a launcher
+ *                     accesses must not straddle a page.
+ *   frame_pool_bytes  HBM budget; n_frames = floor(frame_pool_bytes/page_bytes) >= 2.
+ *   policy            GPUVM_POLICY_FIFO or GPUVM_POLICY_CLOCK.
+ * Allocates (hipMalloc) the frame pool, page table (8 B per page), frame table
+ * (4 B per frame) and counters; all pages start INVALID, all frames empty, the
+ * ring cursor at 0. */
+GPUVM_API int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes,
+                           size_t frame_pool_bytes, int policy, gpuvm_t **out);
+GPUVM_API int gpuvm_destroy(gpuvm_t *vm);
+
+/* Copy of the device-side view, for callers that write their own kernels with
+ * gpuvm_device.h. */
+GPUVM_API int gpuvm_device_handle(const gpuvm_t *vm, gpuvm_dev_t *out);
+
+/* Tuning / test knobs: spin_limit bounds every in-kernel wait (a wave that
+ * exceeds it records GPUVM_EDEADLK and the launch returns it; 0 keeps the
+ * default); access_stats != 0 turns the per-access counters on. */
+GPUVM_API int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats);
+
+/* Wavefronts per compute unit the launchers aim for (1..32, default 8). */
+GPUVM_API int gpuvm_set_waves_per_cu(gpuvm_t *vm, int waves_per_cu);
+
+/* Synchronise `stream` and return the first error a kernel recorded on this
+ * handle since create / reset (GPUVM_OK if none). */
+GPUVM_API int gpuvm_check(gpuvm_t *vm, void *stream);
+
+/* Largest number of wavefronts a launcher will keep in flight on this handle:
+ * each wave holds at most one pinned page plus one frame under migration, so
+ * it is min(n_frames / 2, what the device can hold). */
+GPUVM_API int gpuvm_max_waves(const gpuvm_t *vm);
+
+/* Write every DIRTY page back to host_buf and clear the dirty bits; pages stay
+ * resident (not in the paper, whose write-back happens only at eviction:
+ * Transfer-bound Applications).  Synchronises `stream`; afterwards host_buf is
+ * authoritative and the CPU may read it. */
+GPUVM_API int gpuvm_flush(gpuvm_t *vm, void *stream);
+
+/* gpuvm_flush, then forget every mapping: cold start (all INVALID, frames
+ * empty, cursor 0) and zeroed counters.  Synchronises `stream`. */
+GPUVM_API int gpuvm_reset(gpuvm_t *vm, void *stream);
+
+/* Sum the sharded device counters into *out (host pointer).  Synchronises the
+ * device. */
+GPUVM_API int gpuvm_stats(gpuvm_t *vm, gpuvm_stats_t *out);
+GPUVM_API int gpuvm_stats_clear(gpuvm_t *vm);
+
+/* Copy the raw tables to host arrays for invariant checks: pte_out[n_pages]
+ * (see gpuvm_device.h for the bit layout), owner_out[n_frames] (0xFFFFFFFF =
+ * empty), *hand_out = ring cursor.  Any pointer may be NULL.  Synchronises. */
+GPUVM_API int gpuvm_dump_tables(gpuvm_t *vm, uint64_t *pte_out, uint32_t *owner_out,
+                                uint64_t *hand_out);
+
+GPUVM_API const char *gpuvm_strerror(int code);
+
+/* ---- workload launchers (free-running fault handling) --------------------
+ * Each runs the whole hot path - address split, page-table lookup with
+ * reference count, wavefront dedup, inter-wave fault arbitration, frame
+ * allocation with eviction and dirty write-back, page migration, access,
+ * unpin (paper: System Overview steps 1-7; Paged Memory System Design) -
+ * inside its kernel.  All array arguments are device pointers.  Launches are
+ * asynchronous on `stream` unless stated; a kernel-side GPUVM_EDEADLK is
+ * reported by the next synchronising call on the handle. */
+
+/* Random gather over a uint32 data set: out[k] = data[idx[k]], *sum += sum_k out[k]
+ * (d_sum: one uint64 in device memory, accumulated with atomics; may be NULL).
+ * idx values must be < bytes/4 (checked in the kernel: GPUVM_ERANGE). */
+GPUVM_API int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n,
+                               uint32_t *d_out, uint64_t *d_sum, void *stream);
+
+/* One pass of a streaming read-reduce over an fp32 data set: for each block of
+ * block_elems consecutive floats (a multiple of the page's float count),
+ * d_sums[b] = sum in fp64.  One wavefront per page, consecutive pages to
+ * consecutive wavefronts. */
+GPUVM_API int gpuvm_run_stream_reduce(gpuvm_t *vm, size_t block_elems,
+                                      double *d_sums, void *stream);
+
+/* Level-synchronous BFS; the data set is the int32 col_idx array of a CSR
+ * graph, d_row_ptr[nv+1] (int64) and d_level[nv] (int32 out, -1 = unreachable)
+ * are plain device memory.  One kernel per level; synchronises `stream`
+ * between levels.  *n_levels_out (host, may be NULL) = number of levels run. */
+GPUVM_API int gpuvm_run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv,
+                            int64_t src, int32_t *d_level, int *n_levels_out,
+                            void *stream);
+
+/* Embedding-bag lookup with sum pooling over an fp32 table of `dim` columns
+ * (dim * 4 bytes must divide page_bytes; dim a multiple of 64 up to 256):
+ * d_out[bag][c] = sum_j table[d_ids[bag][j]][c], rows added in listed order in
+ * fp32.  ids must be in [0, bytes/(4*dim)). */
+GPUVM_API int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids,
+                                      size_t bags, size_t bag_len, float *d_out,
+                                      void *stream);
+
+/* Scatter-increment over a uint64 data set: data[idx[k]] += 1 (device atomics
+ * on the frame; pages become DIRTY and reach host_buf at eviction or flush). */
+GPUVM_API int gpuvm_run_scatter_increment(gpuvm_t *vm, const uint32_t *d_idx,
+                                          size_t n, void *stream);
+
+/* ---- deterministic barrier-phased launchers ------------------------------
+ * The same work cut into phases of phase_len consecutive accesses; inside a
+ * phase: (A) all waves dedup, pin resident pages and list missing ones,
+ * (B) one sequential agent serves the missing pages in ascending page order,
+ * walking the ring exactly like a sequential replay, (C) all waves migrate the
+ * assigned pages in parallel, (D) access and unpin.  Fault / eviction /
+ * write-back counts and the final frame table are then unique and must equal
+ * a sequential FIFO / CLOCK replay.  A phase may touch at most n_frames
+ * distinct pages (else GPUVM_EDEADLK).  Synchronise `stream` before returning. */
+GPUVM_API int gpuvm_run_gather_phased(gpuvm_t *vm, const uint32_t *d_idx, size_t n,
+                                      size_t phase_len, uint32_t *d_out,
+                                      uint64_t *d_sum, void *stream);
+GPUVM_API int gpuvm_run_scatter_increment_phased(gpuvm_t *vm, const uint32_t *d_idx,
+                                                 size_t n, size_t phase_len,
+                                                 void *stream);
+
+/* ---- roofline microbenchmarks ---------------------------------------------
+ * The paper's transfer benchmark (Comparison with GPUDirect RDMA: a large
+ * buffer streamed with one page per warp) recast for the wavefront mover:
+ * copy `bytes` from src to dst in chunks of chunk_bytes, one chunk per
+ * wavefront at a time, with `waves` wavefronts in total (0 = as many as the
+ * device holds).  src/dst are device-visible pointers (HBM, or pinned host
+ * memory for the host-link directions).  Asynchronous on `stream`. */
+GPUVM_API int gpuvm_bench_copy(void *dst, const void *src, size_t bytes,
+                               size_t chunk_bytes, int waves, void *stream);
+
+/* Same traffic, reading only (every lane folds what it loaded into one word of
+ * d_sink so the loads cannot be dropped): the read-side link / HBM ceiling. */
+GPUVM_API int gpuvm_bench_read(const void *src, size_t bytes, size_t chunk_bytes,
+                               int waves, uint64_t *d_sink, void *stream);
+
+/* Plain device-resident random gather with no page table (the ceiling for
+ * hits): out[k] = data[idx[k]]. */
+GPUVM_API int gpuvm_bench_gather_plain(const uint32_t *d_data, const uint32_t *d_idx,
+                                       size_t n, uint32_t *d_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPUVM_H */

@@ -1,0 +1,380 @@
+/*
+ * gpuvm_device.h - device-side accessors of GPUVM for gfx950 (HIP only).
+ *
+ * Include from a .hip file, take a gpuvm_dev_t by value as a kernel argument
+ * and index the paged data set like an array (paper: the gpuvm<T> class of the
+ * vector-addition listing; System Overview steps 1-7):
+ *
+ *     float a = gpuvm_load<float>(vm, i);         // any lane, any divergence
+ *     gpuvm_store<float>(vm, i, a + 1.0f);
+ *     gpuvm_atomic_add<unsigned long long>(vm, i, 1ull);
+ *
+ * or, for code in which a whole wavefront works on one page at a time,
+ *
+ *     char *p = gpuvm_acquire(vm, page, write);   // same page in every lane
+ *     ... read / write p[0 .. page_bytes) ...
+ *     gpuvm_release(vm, page, write);
+ *
+ * Execution model.  A CDNA wavefront has no independent thread scheduling, so
+ * the fault path is wave-uniform: the accessor loops over the distinct pages
+ * its active lanes touch (wavefront dedup, paper: Page access
+ * synchronization); for each page the first lane of the group is the leader
+ * and performs every atomic, and all active lanes move the page together (the
+ * substitute for the paper's NIC work request).  A wave pins ONE page at a
+ * time, so pinned frames never exceed the number of waves in flight; the
+ * launchers keep that below half the frame pool, which is what makes "pass
+ * over a pinned frame" always find a victim.
+ *
+ * Page-table word (one 64-bit atomic per page, all updates are atomics that
+ * leave the pin count of concurrent users intact):
+ *     bits  0..31  pin    reference counter: waves that use or wait for the page
+ *     bit   32     REF    CLOCK reference bit
+ *     bit   33     DIRTY  frame differs from host memory
+ *     bits 34..35  state  0 INVALID, 1 LOADING, 2 RESIDENT, 3 EVICTING
+ *     bits 36..63  frame  valid while RESIDENT / EVICTING
+ * Frame table: frame_owner[f] = page whose data the frame holds (0xFFFFFFFF
+ * before first use).  hand[0] is the global head cursor of the frame ring;
+ * ticket t names frame t mod n_frames (paper: Eviction scheme - the leader
+ * atomically takes the next mapping and may not choose a frame).
+ *
+ * Memory ordering.  Page-table atomics are relaxed at agent scope; ordering
+ * comes from fences executed by the whole wave: acquire (agent) after a page
+ * is found RESIDENT and before its frame is read; release (agent) after the
+ * frame was filled or written and before the state word changes; release
+ * (system) after a write-back to host memory and before the victim becomes
+ * INVALID, so that a later fault re-reads the new contents.  Each XCD of the
+ * MI355X has its own L2: the agent-scope fences are what carries frame data
+ * between them.
+ */
+#ifndef GPUVM_DEVICE_H
+#define GPUVM_DEVICE_H
+
+#include <hip/hip_runtime.h>
+#include "gpuvm.h"
+
+#define GPUVM_PTE_PIN_MASK    0x00000000FFFFFFFFull
+#define GPUVM_PTE_REF         (1ull << 32)
+#define GPUVM_PTE_DIRTY       (1ull << 33)
+#define GPUVM_PTE_STATE_SHIFT 34
+#define GPUVM_PTE_STATE_MASK  (3ull << GPUVM_PTE_STATE_SHIFT)
+#define GPUVM_PTE_FRAME_SHIFT 36
+#define GPUVM_ST_INVALID  0ull
+#define GPUVM_ST_LOADING  1ull
+#define GPUVM_ST_RESIDENT 2ull
+#define GPUVM_ST_EVICTING 3ull
+#define GPUVM_NO_PAGE 0xFFFFFFFFu
+
+/* slots of one shard of gpuvm_dev_t::stats (order of gpuvm_stats_t) */
+enum {
+    GPUVM_S_FAULTS = 0, GPUVM_S_EVICTIONS, GPUVM_S_WB_EVICT, GPUVM_S_WB_FLUSH,
+    GPUVM_S_BYTES_IN, GPUVM_S_BYTES_OUT, GPUVM_S_HITS, GPUVM_S_GROUPS,
+    GPUVM_S_COALESCED, GPUVM_S_WAITS, GPUVM_S_SKIPS, GPUVM_S_SWEEPS,
+    GPUVM_S_PHASES, GPUVM_S_COUNT = 16
+};
+
+namespace gpuvm_detail {
+
+#define GPUVM_DEV __device__ __forceinline__
+
+GPUVM_DEV unsigned long long a_load(const unsigned long long *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+GPUVM_DEV unsigned int a_load(const unsigned int *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+GPUVM_DEV void a_store(unsigned int *p, unsigned int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+GPUVM_DEV unsigned long long a_add(unsigned long long *p, unsigned long long v) {
+    return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+GPUVM_DEV unsigned long long a_or(unsigned long long *p, unsigned long long v) {
+    return __hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+GPUVM_DEV unsigned long long a_and(unsigned long long *p, unsigned long long v) {
+    return __hip_atomic_fetch_and(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+GPUVM_DEV unsigned long long a_xor(unsigned long long *p, unsigned long long v) {
+    return __hip_atomic_fetch_xor(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+GPUVM_DEV bool a_cas(unsigned long long *p, unsigned long long *expected, unsigned long long desired) {
+    return __hip_atomic_compare_exchange_strong(p, expected, desired, __ATOMIC_RELAXED,
+                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+GPUVM_DEV void fence_acquire_agent() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
+GPUVM_DEV void fence_release_agent() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+GPUVM_DEV void fence_release_system() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, ""); }
+/* all of this wave's outstanding loads have returned (enough before giving up
+ * a pin on a page that was only read) */
+GPUVM_DEV void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+GPUVM_DEV unsigned int bcast(unsigned int v) { return __builtin_amdgcn_readfirstlane(v); }
+GPUVM_DEV unsigned long long bcast(unsigned long long v) {
+    unsigned int lo = __builtin_amdgcn_readfirstlane((unsigned int)v);
+    unsigned int hi = __builtin_amdgcn_readfirstlane((unsigned int)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+/* the lanes that are executing right now, and this lane's place among them */
+struct wave_t {
+    unsigned long long active;
+    unsigned int rank, count;
+    bool leader;
+};
+GPUVM_DEV wave_t wave_now() {
+    wave_t w;
+    w.active = __builtin_amdgcn_ballot_w64(true);
+    unsigned int below = __builtin_amdgcn_mbcnt_hi((unsigned int)(w.active >> 32),
+                          __builtin_amdgcn_mbcnt_lo((unsigned int)w.active, 0u));
+    w.rank = below;
+    w.count = (unsigned int)__popcll(w.active);
+    w.leader = below == 0;
+    return w;
+}
+
+GPUVM_DEV unsigned long long *stat_shard(const gpuvm_dev_t &vm) {
+    return vm.stats + (size_t)(blockIdx.x & (GPUVM_STAT_SLOTS - 1)) * GPUVM_S_COUNT;
+}
+GPUVM_DEV void stat_add(const gpuvm_dev_t &vm, int which, unsigned long long v) {
+    __hip_atomic_fetch_add(stat_shard(vm) + which, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+/* first error wins; every bounded wait polls this word so that one wave that
+ * gives up releases all the others */
+GPUVM_DEV void raise_error(const gpuvm_dev_t &vm, int code) {
+    unsigned long long expected = 0;
+    a_cas(vm.hand + 1, &expected, (unsigned long long)(unsigned int)(-code));
+}
+GPUVM_DEV bool aborted(const gpuvm_dev_t &vm) { return a_load(vm.hand + 1) != 0; }
+
+GPUVM_DEV unsigned int page_len(const gpuvm_dev_t &vm, unsigned int page) {
+    unsigned long long lo = (unsigned long long)page << vm.page_shift;
+    unsigned long long left = vm.bytes - lo;
+    unsigned long long full = 1ull << vm.page_shift;
+    return (unsigned int)(left < full ? left : full);
+}
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+/* Whole-wave copy: the active lanes move `bytes` from src to dst, 16 bytes per
+ * lane per instruction, lanes on consecutive addresses (one instruction of a
+ * full wave covers 1 KiB), up to 8 loads in flight per lane before the first
+ * store.  This is the page mover (both directions) and the write-back. */
+template <int UNROLL>
+GPUVM_DEV void copy_tier(char *__restrict__ dst, const char *__restrict__ src, unsigned int &o,
+                         unsigned int stride, unsigned int vec_bytes) {
+    for (; o + (UNROLL - 1) * stride < vec_bytes; o += UNROLL * stride) {
+        u32x4 r[UNROLL];
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j)
+            r[j] = *reinterpret_cast<const u32x4 *>(src + o + j * stride);
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j)
+            *reinterpret_cast<u32x4 *>(dst + o + j * stride) = r[j];
+    }
+}
+GPUVM_DEV void wave_copy(char *dst, const char *src, unsigned int bytes, const wave_t &w) {
+    const unsigned int stride = w.count * 16u;
+    const unsigned int vec_bytes = bytes & ~15u;
+    unsigned int o = w.rank * 16u;
+    copy_tier<8>(dst, src, o, stride, vec_bytes);   /* 64 KiB page, full wave: 8 rounds of 8 KiB */
+    copy_tier<4>(dst, src, o, stride, vec_bytes);   /* 4 KiB page, full wave: one round          */
+    copy_tier<2>(dst, src, o, stride, vec_bytes);
+    copy_tier<1>(dst, src, o, stride, vec_bytes);
+    const unsigned int tail = bytes - vec_bytes;    /* < 16 */
+    if (w.rank < tail) dst[vec_bytes + w.rank] = src[vec_bytes + w.rank];
+}
+
+/* Frame allocation + eviction + migration for `page`, whose state word this
+ * wave has just moved INVALID -> LOADING.  Returns the frame, or GPUVM_NO_PAGE
+ * if a bounded wait ran out (error recorded). */
+GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool write, const wave_t &w) {
+    unsigned int f = 0, victim = GPUVM_NO_PAGE, wb = 0, ok = 1;
+    if (w.leader) {
+        unsigned long long skips = 0, sweeps = 0;
+        const unsigned long long budget = 8ull * vm.n_frames + vm.spin_limit;
+        for (unsigned long long tries = 0;; ++tries) {
+            if (tries > budget || ((tries & 1023) == 1023 && aborted(vm))) {
+                raise_error(vm, GPUVM_EDEADLK);
+                ok = 0;
+                break;
+            }
+            const unsigned long long t = a_add(vm.hand, 1ull);
+            f = (unsigned int)(t % vm.n_frames);
+            if (t < vm.n_frames) break;                       /* first turn: frame never used */
+            const unsigned int q = a_load(vm.frame_owner + f);
+            if (q == GPUVM_NO_PAGE) { ++skips; continue; }    /* first install still under way */
+            unsigned long long pq = a_load(vm.pte + q);
+            if (((pq & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT ||
+                (unsigned int)(pq >> GPUVM_PTE_FRAME_SHIFT) != f ||
+                (pq & GPUVM_PTE_PIN_MASK) != 0) { ++skips; continue; }   /* busy or in use */
+            if (vm.policy == GPUVM_POLICY_CLOCK && (pq & GPUVM_PTE_REF)) {
+                a_and(vm.pte + q, ~GPUVM_PTE_REF);            /* second chance */
+                ++sweeps;
+                continue;
+            }
+            /* claim the victim; fails if anybody pinned it in the meantime */
+            if (!a_cas(vm.pte + q, &pq, pq | GPUVM_PTE_STATE_MASK)) { ++skips; continue; }
+            victim = q;
+            wb = (pq & GPUVM_PTE_DIRTY) ? 1u : 0u;
+            break;
+        }
+        if (skips) stat_add(vm, GPUVM_S_SKIPS, skips);
+        if (sweeps) stat_add(vm, GPUVM_S_SWEEPS, sweeps);
+    }
+    ok = bcast(ok);
+    if (!ok) {
+        if (w.leader) a_and(vm.pte + page, GPUVM_PTE_PIN_MASK);          /* back to INVALID */
+        return GPUVM_NO_PAGE;
+    }
+    f = bcast(f); victim = bcast(victim); wb = bcast(wb);
+    char *frame = vm.frames + ((size_t)f << vm.page_shift);
+    if (victim != GPUVM_NO_PAGE) {
+        if (wb) {
+            fence_acquire_agent();                            /* the writers' data */
+            const unsigned int len = page_len(vm, victim);
+            wave_copy(vm.host + ((size_t)victim << vm.page_shift), frame, len, w);
+            fence_release_system();
+            if (w.leader) { stat_add(vm, GPUVM_S_WB_EVICT, 1); stat_add(vm, GPUVM_S_BYTES_OUT, len); }
+        }
+        if (w.leader) {
+            a_and(vm.pte + victim, GPUVM_PTE_PIN_MASK);       /* INVALID; waiters keep their pins */
+            stat_add(vm, GPUVM_S_EVICTIONS, 1);
+        }
+    }
+    const unsigned int len = page_len(vm, page);
+    wave_copy(frame, vm.host + ((size_t)page << vm.page_shift), len, w);
+    if (w.leader) a_store(vm.frame_owner + f, page);
+    fence_release_agent();
+    if (w.leader) {
+        const unsigned long long flip =
+            ((GPUVM_ST_LOADING ^ GPUVM_ST_RESIDENT) << GPUVM_PTE_STATE_SHIFT) |
+            ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) | GPUVM_PTE_REF |
+            (write ? GPUVM_PTE_DIRTY : 0ull);
+        a_xor(vm.pte + page, flip);                           /* publish: RESIDENT */
+        stat_add(vm, GPUVM_S_FAULTS, 1);
+        stat_add(vm, GPUVM_S_BYTES_IN, len);
+    }
+    return f;
+}
+
+}  // namespace gpuvm_detail
+
+/* Pin `page` (the same value in every active lane) and return the address of
+ * its frame, migrating it first if it is not in GPU memory.  `write` = the
+ * caller will modify the page.  Must be followed by gpuvm_release before the
+ * wave acquires another page.  After a recorded error the returned pointer is
+ * a valid dummy (frame 0) so that callers never dereference garbage. */
+__device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned int page_any, bool write) {
+    using namespace gpuvm_detail;
+    const wave_t w = wave_now();
+    const unsigned int page = bcast(page_any);
+    unsigned long long *pte = vm.pte + page;
+    unsigned long long cur = 0;
+    unsigned int how = 0;                     /* 0 hit, 1 this wave faults, 2 gave up */
+    if (w.leader) {
+        cur = a_add(pte, 1ull) + 1ull;        /* lookup and reference count in one atomic */
+        unsigned int spins = 0;
+        for (;;) {
+            const unsigned long long st = (cur & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT;
+            if (st == GPUVM_ST_RESIDENT) break;
+            if (st == GPUVM_ST_INVALID) {     /* inter-wave arbitration: one wave locks the entry */
+                if (a_cas(pte, &cur, cur | (GPUVM_ST_LOADING << GPUVM_PTE_STATE_SHIFT))) { how = 1; break; }
+                continue;
+            }
+            if (spins == 0) stat_add(vm, GPUVM_S_WAITS, 1);
+            if (++spins > vm.spin_limit || ((spins & 63) == 63 && aborted(vm))) {
+                raise_error(vm, GPUVM_EDEADLK);
+                how = 2;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(4);
+            cur = a_load(pte);
+        }
+    }
+    how = bcast(how);
+    if (how == 2) return vm.frames;
+    unsigned int f;
+    if (how == 1) {
+        f = fault(vm, page, write, w);
+        if (f == GPUVM_NO_PAGE) return vm.frames;
+    } else {
+        cur = bcast(cur);
+        f = (unsigned int)(cur >> GPUVM_PTE_FRAME_SHIFT);
+        fence_acquire_agent();
+        if (w.leader) {
+            unsigned long long need = 0;
+            if (write && !(cur & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
+            if (vm.policy == GPUVM_POLICY_CLOCK && !(cur & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
+            if (need) a_or(pte, need);
+            if (vm.flags & GPUVM_F_ACCESS_STATS) stat_add(vm, GPUVM_S_HITS, 1);
+        }
+    }
+    return vm.frames + ((size_t)f << vm.page_shift);
+}
+
+/* Drop the pin taken by gpuvm_acquire.  `wrote` = plain stores went to the
+ * page (they must reach memory before another wave may evict it); reads and
+ * device-scope atomics only need to have completed. */
+__device__ __forceinline__ void gpuvm_release(const gpuvm_dev_t &vm, unsigned int page_any, bool wrote) {
+    using namespace gpuvm_detail;
+    const wave_t w = wave_now();
+    const unsigned int page = bcast(page_any);
+    if (wrote) fence_release_agent(); else wait_loads();
+    if (w.leader) a_add(vm.pte + page, ~0ull);                /* pin - 1 */
+}
+
+/* Element access with wavefront dedup: calls op(T*) once in every active lane
+ * on the lane's element, grouping lanes by page. */
+template <typename T, typename Op>
+__device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write,
+                                             bool plain_stores, Op op) {
+    using namespace gpuvm_detail;
+    const unsigned long long byte = elem * sizeof(T);
+    const unsigned int page = (unsigned int)(byte >> vm.page_shift);              /* address split */
+    const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
+    bool pending = true;
+    for (;;) {
+        const unsigned long long todo = __builtin_amdgcn_ballot_w64(pending);
+        if (todo == 0) break;
+        const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
+        const unsigned int group_page = __builtin_amdgcn_readlane(page, first);
+        const bool mine = pending && page == group_page;
+        if (vm.flags & GPUVM_F_ACCESS_STATS) {
+            const unsigned long long members = __builtin_amdgcn_ballot_w64(mine);
+            if (wave_now().leader) {
+                stat_add(vm, GPUVM_S_GROUPS, 1);
+                stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(members) - 1);
+            }
+        }
+        char *frame = gpuvm_acquire(vm, group_page, write);
+        if (mine) {
+            op(reinterpret_cast<T *>(frame + off));
+            pending = false;
+        }
+        gpuvm_release(vm, group_page, plain_stores);
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ T gpuvm_load(const gpuvm_dev_t &vm, unsigned long long elem) {
+    T v{};
+    gpuvm_access<T>(vm, elem, false, false, [&](T *p) { v = *p; });
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ void gpuvm_store(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
+    gpuvm_access<T>(vm, elem, true, true, [&](T *p) { *p = v; });
+}
+
+/* data[elem] += v with a device-scope atomic on the frame; returns nothing. */
+template <typename T>
+__device__ __forceinline__ void gpuvm_atomic_add(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
+    gpuvm_access<T>(vm, elem, true, false, [&](T *p) {
+        __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    });
+}
+
+#endif /* GPUVM_DEVICE_H */
