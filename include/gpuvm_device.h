@@ -37,14 +37,20 @@
  * ticket t names frame t mod n_frames (paper: Eviction scheme - the leader
  * atomically takes the next mapping and may not choose a frame).
  *
- * Memory ordering.  Page-table atomics are relaxed at agent scope; ordering
- * comes from fences executed by the whole wave: acquire (agent) after a page
- * is found RESIDENT and before its frame is read; release (agent) after the
- * frame was filled or written and before the state word changes; release
- * (system) after a write-back to host memory and before the victim becomes
- * INVALID, so that a later fault re-reads the new contents.  Each XCD of the
- * MI355X has its own L2: the agent-scope fences are what carries frame data
- * between them.
+ * Coherence and ordering.  Each XCD of the MI355X has its own L2, and the
+ * L1/L2 are not kept coherent with each other by hardware for ordinary loads
+ * and stores; agent-scope fences would do it, but they write back / invalidate
+ * a whole L2 each time and serialise the fault path.  Instead every access to
+ * frame memory carries the agent-scope cache bits (sc1): the mover stores the
+ * page write-through, element loads/stores/atomics are relaxed agent-scope
+ * atomics, and wave-level users read frames with gpuvm_frame_load*().  Host
+ * memory is read and written at system scope (sc0 sc1).  Page-table atomics
+ * are relaxed at agent scope.  Ordering then needs no cache maintenance, only
+ * completion: s_waitcnt vmcnt(0) after the page was copied and before it is
+ * published RESIDENT; after a write-back and before the victim becomes INVALID
+ * (the re-fault's reads follow the posted writes on the same link); after a
+ * user's last access and before its pin is dropped.  A reader's frame address
+ * depends on the value its page-table atomic returned.
  */
 #ifndef GPUVM_DEVICE_H
 #define GPUVM_DEVICE_H
@@ -102,12 +108,9 @@ GPUVM_DEV bool a_cas(unsigned long long *p, unsigned long long *expected, unsign
                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-GPUVM_DEV void fence_acquire_agent() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
-GPUVM_DEV void fence_release_agent() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
-GPUVM_DEV void fence_release_system() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, ""); }
-/* all of this wave's outstanding loads have returned (enough before giving up
- * a pin on a page that was only read) */
-GPUVM_DEV void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+/* completion of everything this wave has issued to memory (loads returned,
+ * stores and atomics acknowledged at their scope); also a compiler barrier */
+GPUVM_DEV void wait_vm() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 GPUVM_DEV unsigned int bcast(unsigned int v) { return __builtin_amdgcn_readfirstlane(v); }
 GPUVM_DEV unsigned long long bcast(unsigned long long v) {
@@ -156,34 +159,54 @@ GPUVM_DEV unsigned int page_len(const gpuvm_dev_t &vm, unsigned int page) {
 }
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+/* cache-scope bits of a buffer instruction's aux operand on gfx942/gfx950 */
+#define GPUVM_AUX_AGENT  16   /* sc1: coherent across the XCDs of this GPU */
+#define GPUVM_AUX_SYSTEM 17   /* sc0 sc1: coherent with the host           */
+
+/* Buffer descriptor over [base, base + bytes): raw (stride 0) addressing,
+ * out-of-range lanes read 0 / write nothing. */
+GPUVM_DEV __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned int bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
 
 /* Whole-wave copy: the active lanes move `bytes` from src to dst, 16 bytes per
  * lane per instruction, lanes on consecutive addresses (one instruction of a
  * full wave covers 1 KiB), up to 8 loads in flight per lane before the first
- * store.  This is the page mover (both directions) and the write-back. */
-template <int UNROLL>
-GPUVM_DEV void copy_tier(char *__restrict__ dst, const char *__restrict__ src, unsigned int &o,
+ * store.  This is the page mover (both directions) and the write-back.
+ * LD / ST are the cache scopes of the two sides. */
+template <int UNROLL, int LD, int ST>
+GPUVM_DEV void copy_tier(__amdgpu_buffer_rsrc_t rd, __amdgpu_buffer_rsrc_t rs, unsigned int &o,
                          unsigned int stride, unsigned int vec_bytes) {
     for (; o + (UNROLL - 1) * stride < vec_bytes; o += UNROLL * stride) {
         u32x4 r[UNROLL];
 #pragma unroll
-        for (int j = 0; j < UNROLL; ++j)
-            r[j] = *reinterpret_cast<const u32x4 *>(src + o + j * stride);
+        for (int j = 0; j < UNROLL; ++j) r[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, o + j * stride, 0, LD);
 #pragma unroll
-        for (int j = 0; j < UNROLL; ++j)
-            *reinterpret_cast<u32x4 *>(dst + o + j * stride) = r[j];
+        for (int j = 0; j < UNROLL; ++j) __builtin_amdgcn_raw_buffer_store_b128(r[j], rd, o + j * stride, 0, ST);
     }
 }
+template <int LD, int ST>
 GPUVM_DEV void wave_copy(char *dst, const char *src, unsigned int bytes, const wave_t &w) {
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(src, bytes), rd = make_rsrc(dst, bytes);
     const unsigned int stride = w.count * 16u;
     const unsigned int vec_bytes = bytes & ~15u;
     unsigned int o = w.rank * 16u;
-    copy_tier<8>(dst, src, o, stride, vec_bytes);   /* 64 KiB page, full wave: 8 rounds of 8 KiB */
-    copy_tier<4>(dst, src, o, stride, vec_bytes);   /* 4 KiB page, full wave: one round          */
-    copy_tier<2>(dst, src, o, stride, vec_bytes);
-    copy_tier<1>(dst, src, o, stride, vec_bytes);
-    const unsigned int tail = bytes - vec_bytes;    /* < 16 */
-    if (w.rank < tail) dst[vec_bytes + w.rank] = src[vec_bytes + w.rank];
+    copy_tier<8, LD, ST>(rd, rs, o, stride, vec_bytes);   /* 64 KiB page, full wave: 8 rounds of 8 KiB */
+    copy_tier<4, LD, ST>(rd, rs, o, stride, vec_bytes);   /* 4 KiB page, full wave: one round          */
+    copy_tier<2, LD, ST>(rd, rs, o, stride, vec_bytes);
+    copy_tier<1, LD, ST>(rd, rs, o, stride, vec_bytes);
+    const unsigned int tail = bytes - vec_bytes;          /* < 16 */
+    if (w.rank < tail)
+        __builtin_amdgcn_raw_buffer_store_b8(__builtin_amdgcn_raw_buffer_load_b8(rs, vec_bytes + w.rank, 0, LD),
+                                             rd, vec_bytes + w.rank, 0, ST);
+}
+GPUVM_DEV void copy_host_to_frame(char *frame, const char *host, unsigned int bytes, const wave_t &w) {
+    wave_copy<GPUVM_AUX_SYSTEM, GPUVM_AUX_AGENT>(frame, host, bytes, w);
+}
+GPUVM_DEV void copy_frame_to_host(char *host, const char *frame, unsigned int bytes, const wave_t &w) {
+    wave_copy<GPUVM_AUX_AGENT, GPUVM_AUX_SYSTEM>(host, frame, bytes, w);
 }
 
 /* Frame allocation + eviction + migration for `page`, whose state word this
@@ -232,10 +255,9 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
     char *frame = vm.frames + ((size_t)f << vm.page_shift);
     if (victim != GPUVM_NO_PAGE) {
         if (wb) {
-            fence_acquire_agent();                            /* the writers' data */
             const unsigned int len = page_len(vm, victim);
-            wave_copy(vm.host + ((size_t)victim << vm.page_shift), frame, len, w);
-            fence_release_system();
+            copy_frame_to_host(vm.host + ((size_t)victim << vm.page_shift), frame, len, w);
+            wait_vm();                                        /* posted before the victim can be re-read */
             if (w.leader) { stat_add(vm, GPUVM_S_WB_EVICT, 1); stat_add(vm, GPUVM_S_BYTES_OUT, len); }
         }
         if (w.leader) {
@@ -244,9 +266,9 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
         }
     }
     const unsigned int len = page_len(vm, page);
-    wave_copy(frame, vm.host + ((size_t)page << vm.page_shift), len, w);
+    copy_host_to_frame(frame, vm.host + ((size_t)page << vm.page_shift), len, w);
     if (w.leader) a_store(vm.frame_owner + f, page);
-    fence_release_agent();
+    wait_vm();                                                /* the page is in the frame */
     if (w.leader) {
         const unsigned long long flip =
             ((GPUVM_ST_LOADING ^ GPUVM_ST_RESIDENT) << GPUVM_PTE_STATE_SHIFT) |
@@ -302,7 +324,6 @@ __device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned i
     } else {
         cur = bcast(cur);
         f = (unsigned int)(cur >> GPUVM_PTE_FRAME_SHIFT);
-        fence_acquire_agent();
         if (w.leader) {
             unsigned long long need = 0;
             if (write && !(cur & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
@@ -314,22 +335,33 @@ __device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned i
     return vm.frames + ((size_t)f << vm.page_shift);
 }
 
-/* Drop the pin taken by gpuvm_acquire.  `wrote` = plain stores went to the
- * page (they must reach memory before another wave may evict it); reads and
- * device-scope atomics only need to have completed. */
-__device__ __forceinline__ void gpuvm_release(const gpuvm_dev_t &vm, unsigned int page_any, bool wrote) {
+/* Drop the pin taken by gpuvm_acquire, once everything the wave issued to the
+ * page has completed. */
+__device__ __forceinline__ void gpuvm_release(const gpuvm_dev_t &vm, unsigned int page_any) {
     using namespace gpuvm_detail;
     const wave_t w = wave_now();
     const unsigned int page = bcast(page_any);
-    if (wrote) fence_release_agent(); else wait_loads();
+    wait_vm();
     if (w.leader) a_add(vm.pte + page, ~0ull);                /* pin - 1 */
+}
+
+/* Coherent reads of frame memory for wave-level users of gpuvm_acquire:
+ * `frame` is the pointer gpuvm_acquire returned (the same in every lane),
+ * `byte_off` the lane's offset into the page.  Offsets beyond the page read 0. */
+__device__ __forceinline__ unsigned int gpuvm_frame_load_b32(const gpuvm_dev_t &vm, const char *frame, unsigned int byte_off) {
+    return __builtin_amdgcn_raw_buffer_load_b32(gpuvm_detail::make_rsrc(frame, 1u << vm.page_shift), byte_off, 0, GPUVM_AUX_AGENT);
+}
+__device__ __forceinline__ gpuvm_detail::u32x2 gpuvm_frame_load_b64(const gpuvm_dev_t &vm, const char *frame, unsigned int byte_off) {
+    return __builtin_amdgcn_raw_buffer_load_b64(gpuvm_detail::make_rsrc(frame, 1u << vm.page_shift), byte_off, 0, GPUVM_AUX_AGENT);
+}
+__device__ __forceinline__ gpuvm_detail::u32x4 gpuvm_frame_load_b128(const gpuvm_dev_t &vm, const char *frame, unsigned int byte_off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(gpuvm_detail::make_rsrc(frame, 1u << vm.page_shift), byte_off, 0, GPUVM_AUX_AGENT);
 }
 
 /* Element access with wavefront dedup: calls op(T*) once in every active lane
  * on the lane's element, grouping lanes by page. */
 template <typename T, typename Op>
-__device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write,
-                                             bool plain_stores, Op op) {
+__device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write, Op op) {
     using namespace gpuvm_detail;
     const unsigned long long byte = elem * sizeof(T);
     const unsigned int page = (unsigned int)(byte >> vm.page_shift);              /* address split */
@@ -353,26 +385,35 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
             op(reinterpret_cast<T *>(frame + off));
             pending = false;
         }
-        gpuvm_release(vm, group_page, plain_stores);
+        gpuvm_release(vm, group_page);
     }
 }
 
+/* Elements are 4 or 8 bytes wide and are read, written and updated with
+ * relaxed agent-scope atomics, which is what keeps frame data coherent
+ * between the XCDs without cache maintenance. */
 template <typename T>
 __device__ __forceinline__ T gpuvm_load(const gpuvm_dev_t &vm, unsigned long long elem) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "gpuvm_load: 4- or 8-byte elements");
     T v{};
-    gpuvm_access<T>(vm, elem, false, false, [&](T *p) { v = *p; });
+    gpuvm_access<T>(vm, elem, false, [&](T *p) {
+        v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    });
     return v;
 }
 
 template <typename T>
 __device__ __forceinline__ void gpuvm_store(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
-    gpuvm_access<T>(vm, elem, true, true, [&](T *p) { *p = v; });
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "gpuvm_store: 4- or 8-byte elements");
+    gpuvm_access<T>(vm, elem, true, [&](T *p) {
+        __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    });
 }
 
 /* data[elem] += v with a device-scope atomic on the frame; returns nothing. */
 template <typename T>
 __device__ __forceinline__ void gpuvm_atomic_add(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
-    gpuvm_access<T>(vm, elem, true, false, [&](T *p) {
+    gpuvm_access<T>(vm, elem, true, [&](T *p) {
         __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     });
 }

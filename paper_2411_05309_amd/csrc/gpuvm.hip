@@ -82,14 +82,14 @@ __global__ __launch_bounds__(kBlock) void k_flush(gpuvm_dev_t vm) {
             (unsigned int)(pq >> GPUVM_PTE_FRAME_SHIFT) != f || !(pq & GPUVM_PTE_DIRTY))
             continue;
         const unsigned int len = page_len(vm, q);
-        wave_copy(vm.host + ((size_t)q << vm.page_shift), vm.frames + ((size_t)f << vm.page_shift), len, w);
+        copy_frame_to_host(vm.host + ((size_t)q << vm.page_shift), vm.frames + ((size_t)f << vm.page_shift), len, w);
         if (w.leader) {
             a_and(vm.pte + q, ~GPUVM_PTE_DIRTY);
             stat_add(vm, GPUVM_S_WB_FLUSH, 1);
             stat_add(vm, GPUVM_S_BYTES_OUT, len);
         }
     }
-    fence_release_system();
+    wait_vm();
 }
 
 // ------------------------------------------------------------------ workload kernels
@@ -140,18 +140,19 @@ __global__ __launch_bounds__(kBlock) void k_stream_reduce(gpuvm_dev_t vm, unsign
     const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
     const unsigned int nwaves = (gridDim.x * kBlock) >> 6;
     for (unsigned int page = wave; page < vm.n_pages; page += nwaves) {
-        const unsigned int nvec = page_len(vm, page) >> 4;            // float4 items
-        const float4 *p = reinterpret_cast<const float4 *>(gpuvm_acquire(vm, page, false));
+        const unsigned int len = page_len(vm, page);
+        const unsigned int nvec = len >> 4;                           // float4 items
+        const char *p = gpuvm_acquire(vm, page, false);
         double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
         for (unsigned int i = lane; i < nvec; i += 64) {
-            const float4 v = p[i];
-            a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
+            const u32x4 v = gpuvm_frame_load_b128(vm, p, i << 4);
+            a0 += (double)__uint_as_float(v.x); a1 += (double)__uint_as_float(v.y);
+            a2 += (double)__uint_as_float(v.z); a3 += (double)__uint_as_float(v.w);
         }
         // floats beyond the last full float4 of a short last page
-        const unsigned int nfl = page_len(vm, page) >> 2;
-        const float *pf = reinterpret_cast<const float *>(p);
-        if ((nvec << 2) + lane < nfl) a0 += (double)pf[(nvec << 2) + lane];
-        gpuvm_release(vm, page, false);
+        if ((nvec << 4) + (lane << 2) < len)
+            a0 += (double)__uint_as_float(gpuvm_frame_load_b32(vm, p, (nvec << 4) + (lane << 2)));
+        gpuvm_release(vm, page);
         double s = (a0 + a1) + (a2 + a3);
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(kBlock) void k_bfs_level(gpuvm_dev_t vm, const int6
         if (v < nv && level[v] == cur) { beg = row_ptr[v]; end = row_ptr[v + 1]; }
         unsigned long long todo = __builtin_amdgcn_ballot_w64(end > beg);
         unsigned int held = GPUVM_NO_PAGE;
-        const int32_t *ptr = nullptr;
+        const char *ptr = nullptr;
         while (todo) {
             const unsigned int l = (unsigned int)__ffsll((long long)todo) - 1u;
             todo &= todo - 1;
@@ -190,18 +191,18 @@ __global__ __launch_bounds__(kBlock) void k_bfs_level(gpuvm_dev_t vm, const int6
                 const int64_t page_stop = page_first + ((int64_t)1 << elems_shift);
                 const int64_t stop = e < page_stop ? e : page_stop;
                 if (page != held) {
-                    if (held != GPUVM_NO_PAGE) gpuvm_release(vm, held, false);
-                    ptr = reinterpret_cast<const int32_t *>(gpuvm_acquire(vm, page, false));
+                    if (held != GPUVM_NO_PAGE) gpuvm_release(vm, held);
+                    ptr = gpuvm_acquire(vm, page, false);
                     held = page;
                 }
                 for (int64_t i = pos + lane; i < stop; i += 64) {
-                    const int32_t u = ptr[i - page_first];
+                    const int32_t u = (int32_t)gpuvm_frame_load_b32(vm, ptr, (unsigned int)(i - page_first) << 2);
                     if (level[u] < 0) { level[u] = cur + 1; found = 1; }
                 }
                 pos = stop;
             }
         }
-        if (held != GPUVM_NO_PAGE) gpuvm_release(vm, held, false);
+        if (held != GPUVM_NO_PAGE) gpuvm_release(vm, held);
     }
     if (__builtin_amdgcn_ballot_w64(found != 0) && lane == 0) *changed = 1;
 }
@@ -230,8 +231,19 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
                 const unsigned int page = (unsigned int)(byte >> vm.page_shift);
                 const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
                 const char *p = gpuvm_acquire(vm, page, false);
-                const vec_t v = *reinterpret_cast<const vec_t *>(p + off + lane * (VPL * 4u));
-                gpuvm_release(vm, page, false);
+                vec_t v;
+                const unsigned int o = off + lane * (VPL * 4u);
+                if constexpr (VPL == 1) {
+                    v = __uint_as_float(gpuvm_frame_load_b32(vm, p, o));
+                } else if constexpr (VPL == 2) {
+                    const u32x2 r = gpuvm_frame_load_b64(vm, p, o);
+                    v.x = __uint_as_float(r.x); v.y = __uint_as_float(r.y);
+                } else {
+                    const u32x4 r = gpuvm_frame_load_b128(vm, p, o);
+                    v.x = __uint_as_float(r.x); v.y = __uint_as_float(r.y);
+                    v.z = __uint_as_float(r.z); v.w = __uint_as_float(r.w);
+                }
+                gpuvm_release(vm, page);
                 acc += v;
             }
         }
@@ -249,7 +261,7 @@ __global__ __launch_bounds__(kBlock) void k_bench_copy(char *dst, const char *sr
     for (size_t c = wave; c < nchunks; c += nwaves) {
         const size_t lo = c * chunk;
         const unsigned int len = (unsigned int)(chunk < bytes - lo ? chunk : bytes - lo);
-        wave_copy(dst + lo, src + lo, len, w);
+        wave_copy<GPUVM_AUX_SYSTEM, GPUVM_AUX_SYSTEM>(dst + lo, src + lo, len, w);
     }
 }
 
@@ -378,10 +390,11 @@ __global__ __launch_bounds__(kBlock) void k_phase_migrate(gpuvm_dev_t vm, const 
         const phase_job job = jobs[j];
         char *frame = vm.frames + ((size_t)job.frame << vm.page_shift);
         if (job.writeback)
-            wave_copy(vm.host + ((size_t)job.victim << vm.page_shift), frame, page_len(vm, job.victim), w);
-        wave_copy(frame, vm.host + ((size_t)job.page << vm.page_shift), page_len(vm, job.page), w);
+            copy_frame_to_host(vm.host + ((size_t)job.victim << vm.page_shift), frame, page_len(vm, job.victim), w);
+        if (job.writeback) wait_vm();
+        copy_host_to_frame(frame, vm.host + ((size_t)job.page << vm.page_shift), page_len(vm, job.page), w);
     }
-    fence_release_system();
+    wait_vm();
 }
 
 // (D) the accesses themselves (every page of the phase is resident and pinned),
@@ -399,7 +412,7 @@ __global__ __launch_bounds__(kBlock) void k_phase_access(gpuvm_dev_t vm, const u
         const unsigned long long pq = a_load(vm.pte + page);
         char *p = vm.frames + ((size_t)(pq >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off;
         if (OP == 0) {
-            const uint32_t v = *reinterpret_cast<const uint32_t *>(p);
+            const uint32_t v = __hip_atomic_load(reinterpret_cast<const uint32_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             out[i] = v;
             acc = v;
         } else {
