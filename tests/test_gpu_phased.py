@@ -1,0 +1,95 @@
+"""Deterministic barrier-phased mode: fault / hit / eviction / write-back
+counts, ring cursor and the final frame table must equal the oracle's
+sequential FIFO / CLOCK replay, and the application output its definition."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2411_05309_amd as gv
+from paper_2411_05309_amd import inputs
+
+from gpu_util import Backing, check_invariants, dev, host
+
+pytestmark = pytest.mark.gpu
+
+_POL = {gv.POLICY_FIFO: oracle.FIFO, gv.POLICY_CLOCK: oracle.CLOCK}
+
+
+def _compare_with_replay(b, sim, frames):
+    st, f, owner, hand = check_invariants(b, read_only=False)
+    c = sim.counters
+    for gpu_name, sim_name in [("faults", "faults"), ("hits", "hits"), ("evictions", "evictions"),
+                               ("writebacks_evict", "writebacks_evict"), ("alloc_skips", "skips"),
+                               ("alloc_sweeps", "sweeps"), ("phases", "phases")]:
+        assert st[gpu_name] == c[sim_name], (gpu_name, st, c)
+    s = sim.state()
+    want_owner = np.where(s["owner"] < 0, gv.NO_PAGE, s["owner"]).astype(np.uint32)
+    assert np.array_equal(owner, want_owner)
+    assert hand % frames == sim.hand
+    res = np.nonzero(f["state"] == gv.ST_RESIDENT)[0]
+    assert np.array_equal(f["frame"][res], s["where"][res])
+    assert np.array_equal(f["dirty"][res], s["dirty"][s["where"][res]])
+    assert np.array_equal(f["ref"][res], s["ref"][s["where"][res]])
+    return st
+
+
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO])
+@pytest.mark.parametrize("n_elems,page,frames,n_idx,phase_len", [
+    (1 << 18, 4096, 64, 20000, 48),        # 256 pages over 64 frames, phases pin most of the pool
+    ((1 << 16) + 100, 4096, 16, 5003, 7),  # short last page, ragged last phase
+    (1 << 16, 4096, 128, 4000, 64),        # fits
+    (1 << 20, 4096, 256, 30000, 200),
+])
+def test_gather_phased_equals_sequential_replay(gpu, policy, n_elems, page, frames, n_idx, phase_len):
+    data = inputs.u32_values(1, 0, n_elems)
+    # skewed indices so that CLOCK and FIFO differ and pinned frames are passed over
+    r = inputs.zipf_ranks(4, 0, n_idx, n_elems, 1.2) - 1
+    idx = ((r * 2654435761) % n_elems).astype(np.uint32)
+    want, want_sum = oracle.gather(data, idx)
+    sim = oracle.PagingSim(page // 8, frames, _POL[policy], n_words=-(-data.nbytes // 8))
+    sim.run((idx.astype(np.uint64) * 4) // 8, phase_len=phase_len)
+    with Backing(data, page, frames * page, policy) as b:
+        d_idx = dev(idx)
+        d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
+        d_sum = torch.zeros(1, dtype=torch.int64, device="cuda")
+        gv.gpuvm_run_gather_phased(b.vm, d_idx, n_idx, phase_len, d_out, d_sum)
+        assert np.array_equal(host(d_out, np.uint32), want)
+        assert int(host(d_sum, np.uint64)[0]) == want_sum
+        st = _compare_with_replay(b, sim, frames)
+        assert st["writebacks_evict"] == 0
+        assert np.array_equal(b.arr, data)
+
+
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO])
+@pytest.mark.parametrize("n_elems,page,frames,n_upd,phase_len", [
+    (1 << 15, 4096, 16, 20000, 12),
+    ((1 << 14) + 9, 4096, 8, 6001, 5),
+])
+def test_scatter_phased_equals_sequential_replay(gpu, policy, n_elems, page, frames, n_upd, phase_len):
+    r = inputs.zipf_ranks(6, 0, n_upd, n_elems, 0.9) - 1
+    idx = ((r * 40503) % n_elems).astype(np.uint32)
+    want = np.zeros(n_elems, np.uint64)
+    sim = oracle.PagingSim(page // 8, frames, _POL[policy], host=want)
+    sim.run(idx.astype(np.uint64), op=oracle.ADD, val=1, phase_len=phase_len)
+    with Backing(np.zeros(n_elems, np.uint64), page, frames * page, policy) as b:
+        gv.gpuvm_run_scatter_increment_phased(b.vm, dev(idx), n_upd, phase_len)
+        st = _compare_with_replay(b, sim, frames)
+        assert st["writebacks_evict"] > 0
+        gv.gpuvm_flush(b.vm)
+        sim.flush()
+        assert gv.gpuvm_stats(b.vm)["writebacks_flush"] == sim.counters["writebacks_flush"]
+        assert np.array_equal(b.arr, want)
+        direct = np.zeros(n_elems, np.uint64)
+        oracle.scatter_increment(direct, idx)
+        assert np.array_equal(b.arr, direct)
+
+
+def test_phase_with_more_pages_than_frames_is_refused(gpu):
+    data = inputs.u32_values(1, 0, 1 << 16)
+    with Backing(data, 4096, 8 * 4096) as b:
+        idx = (np.arange(32, dtype=np.uint32) * 1024)            # 32 distinct pages, 8 frames
+        d_out = torch.zeros(32, dtype=torch.int32, device="cuda")
+        with pytest.raises(gv.GpuvmError) as e:
+            gv.gpuvm_run_gather_phased(b.vm, dev(idx), 32, 32, d_out, None)
+        assert e.value.code == gv.EDEADLK
