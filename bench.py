@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--policy", default="clock", choices=["clock", "fifo"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
     return ap.parse_args()
 
 
@@ -74,6 +75,20 @@ def measure_link(gv, torch, np):
     e0.record(); gv.gpuvm_bench_copy(d2, d, nbytes, 65536, 4096); e1.record()
     torch.cuda.synchronize()
     res["hbm_copy_rw"] = round(2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    # both directions at once (two streams of default priority): the ceiling for
+    # a fault that writes a dirty victim back while other waves fetch
+    h2 = gv.pinned_array((nbytes,), np.uint8)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    best = 0.0
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        gv.gpuvm_bench_copy(d, h, nbytes, 65536, 1024, stream=s1)
+        gv.gpuvm_bench_copy(h2, d2, nbytes, 65536, 1024, stream=s2)
+        torch.cuda.synchronize()
+        best = max(best, nbytes / (time.perf_counter() - t0) / 1e9)
+    res["duplex_each_direction"] = round(best, 2)
+    gv.free_pinned(h2)
     del d, d2, ht
     gv.free_pinned(h)
     return res
@@ -172,7 +187,8 @@ class BfsWorkload:
     level live in plain HBM."""
     scale, edge_factor, page = 26, 16, 65536
     dtype = "i32"
-    kernel = "k_bfs_level"
+    kernel = "k_bfs_level_balanced"
+    naive = False                                    # True: vertex-chunk work distribution (plain CSR)
 
     def __init__(self, gv, torch, np, inputs, policy, scale=None):
         self.gv, self.torch, self.np = gv, torch, np
@@ -193,7 +209,8 @@ class BfsWorkload:
         self.useful_bytes = None                      # edges actually traversed * 4, filled by verify
 
     def launch(self):
-        self.levels = self.gv.gpuvm_run_bfs(self.vm, self.d_rp, self.nv, 0, self.d_level)
+        run = self.gv.gpuvm_run_bfs if self.naive else self.gv.gpuvm_run_bfs_balanced
+        self.levels = run(self.vm, self.d_rp, self.nv, 0, self.d_level)
 
     def verify(self, oracle):
         np = self.np
@@ -359,6 +376,9 @@ def main():
     if args.warmup is None:
         args.warmup = DEFAULT_STEPS[args.workload][1]
     W = WORKLOADS[args.workload](gv, torch, np, inputs, policy)
+    if args.workload == "bfs" and args.bfs_naive:
+        W.naive, W.kernel = True, "k_bfs_level"
+        W.name += "_vertex_chunks"
     if args.waves_per_cu:
         gv.gpuvm_set_waves_per_cu(W.vm, args.waves_per_cu)
 

@@ -190,6 +190,16 @@ GPUVM_API int gpuvm_run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv,
                             int64_t src, int32_t *d_level, int *n_levels_out,
                             void *stream);
 
+/* The same BFS with the work cut into equal chunks of edges instead of
+ * vertices (paper: Graph Workloads, Balanced CSR - an even number of faults
+ * per worker, no serialisation behind huge neighbour lists): a wavefront owns
+ * one page of col_idx per level and walks the segments of the frontier's
+ * vertices inside it.  Same arguments and result as gpuvm_run_bfs; the
+ * row_ptr array must be non-decreasing with row_ptr[nv] = bytes / 4. */
+GPUVM_API int gpuvm_run_bfs_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv,
+                                     int64_t src, int32_t *d_level, int *n_levels_out,
+                                     void *stream);
+
 /* Embedding-bag lookup with sum pooling over an fp32 table of `dim` columns
  * (dim * 4 bytes must divide page_bytes; dim a multiple of 64 up to 256):
  * d_out[bag][c] = sum_j table[d_ids[bag][j]][c], rows added in listed order in

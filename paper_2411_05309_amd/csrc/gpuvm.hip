@@ -47,6 +47,7 @@ struct gpuvm {
     size_t phase_cap = 0;
     unsigned int phase_tag = 0;
     int *bfs_changed = nullptr;
+    unsigned int *page_owner = nullptr;   // [n_pages + 1], edge-balanced BFS
 };
 
 #define HIP_TRY(expr)                                                            \
@@ -203,6 +204,81 @@ __global__ __launch_bounds__(kBlock) void k_bfs_level(gpuvm_dev_t vm, const int6
             }
         }
         if (held != GPUVM_NO_PAGE) gpuvm_release(vm, held);
+    }
+    if (__builtin_amdgcn_ballot_w64(found != 0) && lane == 0) *changed = 1;
+}
+
+// ---- edge-balanced BFS (the paper's Balanced CSR idea, Graph Workloads: equal
+// chunks of edges per worker so that faults do not serialise behind the huge
+// neighbour lists).  The chunk is one page of col_idx: a wave owns page p for
+// the level, so every page is faulted by at most one wave per level and no
+// vertex, however large, is walked by a single wave.
+// page_owner[p] = vertex that owns the first edge of page p (owner[n_pages] = nv-1).
+__global__ void k_bfs_page_owner(const int64_t *__restrict__ row_ptr, int64_t nv, unsigned int n_pages,
+                                 unsigned int elems_shift, unsigned int *page_owner) {
+    const unsigned int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > n_pages) return;
+    if (p == n_pages) { page_owner[p] = (unsigned int)(nv - 1); return; }
+    const int64_t e = (int64_t)p << elems_shift;
+    int64_t lo = 0, hi = nv;                      // last v with row_ptr[v] <= e
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (row_ptr[mid] <= e) lo = mid; else hi = mid;
+    }
+    page_owner[p] = (unsigned int)lo;
+}
+
+__global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
+                                                                const unsigned int *__restrict__ page_owner,
+                                                                int32_t *level, int32_t cur, int *changed) {
+    const unsigned int lane = threadIdx.x & 63;
+    const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const unsigned int nwaves = (gridDim.x * kBlock) >> 6;
+    const unsigned int elems_shift = vm.page_shift - 2;
+    const int64_t n_edges = (int64_t)(vm.bytes >> 2);
+    constexpr int kSmall = 32;                    // lists up to this length: one lane each
+    int found = 0;
+    for (unsigned int page = wave; page < vm.n_pages; page += nwaves) {
+        const int64_t e_lo = (int64_t)page << elems_shift;
+        const int64_t e_hi = min((long long)n_edges, (long long)(e_lo + ((int64_t)1 << elems_shift)));
+        const int64_t v_first = page_owner[page], v_last = page_owner[page + 1];
+        const char *ptr = nullptr;
+        for (int64_t vb = v_first; vb <= v_last; vb += 64) {
+            const int64_t v = vb + lane;
+            int64_t beg = 0, end = 0;
+            if (v <= v_last && level[v] == cur) {
+                beg = max((long long)row_ptr[v], (long long)e_lo);
+                end = min((long long)row_ptr[v + 1], (long long)e_hi);
+            }
+            const int len = end > beg ? (int)(end - beg) : 0;
+            if (__builtin_amdgcn_ballot_w64(len > 0) == 0) continue;
+            if (!ptr) ptr = gpuvm_acquire(vm, page, false);
+            // short lists: every lane walks its own vertex's segment
+            const bool small = len > 0 && len <= kSmall;
+            int longest = small ? len : 0;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) longest = max(longest, __shfl_xor(longest, off, 64));
+            const unsigned int my_off = (unsigned int)(beg - e_lo) << 2;
+            for (int j = 0; j < longest; ++j) {
+                if (small && j < len) {
+                    const int32_t u = (int32_t)gpuvm_frame_load_b32(vm, ptr, my_off + ((unsigned int)j << 2));
+                    if (level[u] < 0) { level[u] = cur + 1; found = 1; }
+                }
+            }
+            // long lists: the whole wave walks one segment at a time
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(len > kSmall);
+            while (todo) {
+                const unsigned int l = (unsigned int)__ffsll((long long)todo) - 1u;
+                todo &= todo - 1;
+                const unsigned int off0 = (unsigned int)__builtin_amdgcn_readlane((int)my_off, l);
+                const unsigned int n = (unsigned int)__builtin_amdgcn_readlane(len, l);
+                for (unsigned int i = lane; i < n; i += 64) {
+                    const int32_t u = (int32_t)gpuvm_frame_load_b32(vm, ptr, off0 + (i << 2));
+                    if (level[u] < 0) { level[u] = cur + 1; found = 1; }
+                }
+            }
+        }
+        if (ptr) gpuvm_release(vm, page);
     }
     if (__builtin_amdgcn_ballot_w64(found != 0) && lane == 0) *changed = 1;
 }
@@ -602,7 +678,7 @@ int gpuvm_destroy(gpuvm_t *vm) {
     gpuvm_dev_t &d = vm->dev;
     (void)hipFree(d.frames); (void)hipFree(d.pte); (void)hipFree(d.frame_owner); (void)hipFree(d.hand); (void)hipFree(d.stats);
     (void)hipFree(vm->stamp); (void)hipFree(vm->first); (void)hipFree(vm->miss); (void)hipFree(vm->miss_sorted); (void)hipFree(vm->jobs);
-    (void)hipFree(vm->phase_ctr); (void)hipFree(vm->bfs_changed);
+    (void)hipFree(vm->phase_ctr); (void)hipFree(vm->bfs_changed); (void)hipFree(vm->page_owner);
     delete vm;
     return GPUVM_OK;
 }
@@ -732,20 +808,30 @@ int gpuvm_run_stream_reduce(gpuvm_t *vm, size_t block_elems, double *d_sums, voi
     return GPUVM_OK;
 }
 
-int gpuvm_run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
-                  int *n_levels_out, void *stream) {
+static int run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
+                   int *n_levels_out, void *stream, bool balanced) {
     if (!vm || !d_row_ptr || !d_level || nv <= 0 || src < 0 || src >= nv || nv > 0x7FFFFFFF) return GPUVM_EINVAL;
     if (vm->dev.bytes % 4) return GPUVM_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    const int waves = launch_waves(vm, (size_t)((nv + 63) / 64));
+    const int waves = launch_waves(vm, balanced ? (size_t)vm->dev.n_pages : (size_t)((nv + 63) / 64));
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    if (balanced) {
+        if (!vm->page_owner) HIP_TRY(hipMalloc(&vm->page_owner, ((size_t)vm->dev.n_pages + 1) * sizeof(unsigned int)));
+        const unsigned int n = vm->dev.n_pages + 1;
+        k_bfs_page_owner<<<(n + 255) / 256, 256, 0, s>>>(d_row_ptr, nv, vm->dev.n_pages, vm->dev.page_shift - 2,
+                                                         vm->page_owner);
+    }
     k_fill32<<<1024, 256, 0, s>>>((unsigned int *)d_level, (size_t)nv, 0xFFFFFFFFu);
     k_fill32<<<1, 64, 0, s>>>((unsigned int *)d_level + src, 1, 0u);
     int levels = 0;
     for (int32_t cur = 0;; ++cur) {
         int changed = 0;
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
-        k_bfs_level<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, nv, d_level, cur, vm->bfs_changed);
+        if (balanced)
+            k_bfs_level_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, d_level,
+                                                                           cur, vm->bfs_changed);
+        else
+            k_bfs_level<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, nv, d_level, cur, vm->bfs_changed);
         HIP_TRY(hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         ++levels;
@@ -755,6 +841,16 @@ int gpuvm_run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src
     }
     if (n_levels_out) *n_levels_out = levels;
     return check_kernel_error(vm);
+}
+
+int gpuvm_run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
+                  int *n_levels_out, void *stream) {
+    return run_bfs(vm, d_row_ptr, nv, src, d_level, n_levels_out, stream, false);
+}
+
+int gpuvm_run_bfs_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
+                           int *n_levels_out, void *stream) {
+    return run_bfs(vm, d_row_ptr, nv, src, d_level, n_levels_out, stream, true);
 }
 
 int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids, size_t bags, size_t bag_len,

@@ -51,13 +51,14 @@ def test_stream_reduce(gpu, n_floats, page, frames, block_pages):
 
 # ---------------------------------------------------------------- BFS
 
-def _bfs_case(rp, ci, src, page, frames, policy=gv.POLICY_CLOCK):
+def _bfs_case(rp, ci, src, page, frames, policy=gv.POLICY_CLOCK, balanced=False):
     nv = rp.size - 1
     want = oracle.bfs(rp, ci, src)
+    run = gv.gpuvm_run_bfs_balanced if balanced else gv.gpuvm_run_bfs
     with Backing(ci, page, frames * page, policy) as b:
         d_rp = dev(rp)
         d_level = torch.zeros(nv, dtype=torch.int32, device="cuda")
-        levels = gv.gpuvm_run_bfs(b.vm, d_rp, nv, src, d_level)
+        levels = run(b.vm, d_rp, nv, src, d_level)
         got = d_level.cpu().numpy()
         assert np.array_equal(got, want)
         assert levels == want.max() + 1
@@ -65,25 +66,37 @@ def _bfs_case(rp, ci, src, page, frames, policy=gv.POLICY_CLOCK):
     return st
 
 
-@pytest.mark.parametrize("scale,page,frames", [(14, 4096, 16), (16, 65536, 16), (12, 4096, 512)])
-def test_bfs_rmat(gpu, scale, page, frames):
+@pytest.mark.parametrize("balanced", [False, True])
+@pytest.mark.parametrize("scale,page,frames", [(14, 4096, 16), (16, 65536, 16), (12, 4096, 512), (17, 4096, 64)])
+def test_bfs_rmat(gpu, scale, page, frames, balanced):
     rp, ci = inputs.rmat_csr(5, scale)
-    st = _bfs_case(rp, ci, 0, page, frames)
+    st = _bfs_case(rp, ci, 0, page, frames, balanced=balanced)
     assert st["faults"] > 0
+    if balanced:
+        assert st["loading_waits"] == 0          # a page belongs to one wave per level
 
 
-def test_bfs_special_graphs(gpu):
+@pytest.mark.parametrize("balanced", [False, True])
+def test_bfs_special_graphs(gpu, balanced):
     n = 5000                                                       # long path: many levels
     src = np.arange(n - 1)
     rp = np.concatenate([np.arange(n), [n - 1]]).astype(np.int64)
     ci = (src + 1).astype(np.int32)
-    _bfs_case(rp[:n + 1], ci, 0, 4096, 8)
+    _bfs_case(rp[:n + 1], ci, 0, 4096, 8, balanced=balanced)
     nv = 3000                                                      # star with a huge hub + unreachable tail
     rp = np.zeros(nv + 1, np.int64)
     rp[1:] = 2500
     ci = np.arange(1, 2501, dtype=np.int32)
-    _bfs_case(rp, ci, 0, 4096, 8)
-    _bfs_case(rp, ci, 7, 4096, 8)                                  # source without edges
+    _bfs_case(rp, ci, 0, 4096, 8, balanced=balanced)
+    _bfs_case(rp, ci, 7, 4096, 8, balanced=balanced)               # source without edges
+    # many empty rows before, between and after the only rows that have edges
+    nv = 100000
+    rp = np.zeros(nv + 1, np.int64)
+    rp[50001:] = 3000
+    rp[90001:] = 3010
+    ci = np.concatenate([np.arange(60000, 63000), np.full(10, 50000)]).astype(np.int32)
+    _bfs_case(rp, ci, 50000, 4096, 8, balanced=balanced)
+    _bfs_case(rp, ci, 90000, 4096, 8, balanced=balanced)
 
 
 # ---------------------------------------------------------------- embedding bag
