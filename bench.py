@@ -133,6 +133,70 @@ class GatherWorkload:
     def config(self):
         return {"elements": self.n_elems, "indices": self.n_idx}
 
+    def baselines(self, oracle):
+        """The same gather with no paging layer: (a) zero-copy, the kernel
+        dereferences the mapped pinned host array directly; (b) hipMallocManaged
+        memory.  XNACK demand paging is not available on this machine, so (b) is
+        what the runtime does without it (no page migration on fault)."""
+        gv, torch, np = self.gv, self.torch, self.np
+        want, _ = oracle.gather(self.data, self.idx)
+        res = {}
+
+        def timed(ptr):
+            ts = []
+            for _ in range(4):
+                self.d_out.zero_()
+                torch.cuda.synchronize()
+                e0, e1 = ev_pair(torch)
+                e0.record()
+                gv.gpuvm_bench_gather_plain(ptr, self.d_idx, self.n_idx, self.d_out)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            ok = bool(np.array_equal(self.d_out.cpu().numpy().view(np.uint32), want))
+            return {"first_ms": round(ts[0], 4), "best_ms": round(min(ts), 4), "parity": ok}
+
+        # hit path: the same gather when every page is resident (pool = data set, warm)
+        vm2 = gv.gpuvm_create(self.arr.ctypes.data, self.arr.nbytes, self.page, self.arr.nbytes, 1)
+        try:
+            for _ in range(2):
+                gv.gpuvm_run_gather(vm2, self.d_idx, self.n_idx, self.d_out, None)
+            gv.gpuvm_check(vm2)
+            f0 = gv.gpuvm_stats(vm2)["faults"]
+            ts = []
+            for _ in range(5):
+                torch.cuda.synchronize()
+                e0, e1 = ev_pair(torch)
+                e0.record()
+                gv.gpuvm_run_gather(vm2, self.d_idx, self.n_idx, self.d_out, None)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            res["gpuvm_all_resident_hits_only"] = {
+                "best_ms": round(min(ts), 4), "new_faults": gv.gpuvm_stats(vm2)["faults"] - f0,
+                "G_elem_per_s": round(self.n_idx / (min(ts) * 1e-3) / 1e9, 3),
+                "parity": bool(np.array_equal(self.d_out.cpu().numpy().view(np.uint32), want))}
+        finally:
+            gv.gpuvm_destroy(vm2)
+        res["zero_copy_pinned_host"] = timed(self.arr.ctypes.data)
+        dd = torch.from_numpy(self.data.view(np.int32)).cuda()
+        res["resident_in_hbm_no_paging"] = timed(dd.data_ptr())
+        try:
+            import ctypes
+            hip = ctypes.CDLL("libamdhip64.so")
+            p = ctypes.c_void_p()
+            rc = hip.hipMallocManaged(ctypes.byref(p), ctypes.c_size_t(self.arr.nbytes), ctypes.c_uint(1))
+            if rc != 0 or not p.value:
+                raise RuntimeError(f"hipMallocManaged rc={rc}")
+            ctypes.memmove(p.value, self.arr.ctypes.data, self.arr.nbytes)
+            r = timed(p.value)
+            r["note"] = "hipMallocManaged without XNACK (demand paging unavailable on this pool)"
+            res["managed_no_xnack"] = r
+            hip.hipFree(p)
+        except Exception as exc:                     # report, never substitute
+            res["managed_no_xnack"] = {"error": str(exc)}
+        return res
+
 
 class StreamWorkload:
     """Streaming read-reduce: 8 GiB fp32 host array, 64 KiB pages, 2 GiB pool, 3 passes."""
@@ -445,6 +509,8 @@ def main():
             "hbm_copy_measured_GBps": link["hbm_copy_rw"],
         },
     }
+    if hasattr(W, "baselines"):
+        out["baselines_same_gpu"] = W.baselines(oracle)
     if not args.no_cpu_baseline:
         cpu_s, sample = W.cpu_baseline(oracle)
         out["cpu_baseline"] = {

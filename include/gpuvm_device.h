@@ -359,29 +359,79 @@ __device__ __forceinline__ gpuvm_detail::u32x4 gpuvm_frame_load_b128(const gpuvm
 }
 
 /* Element access with wavefront dedup: calls op(T*) once in every active lane
- * on the lane's element, grouping lanes by page. */
+ * on the lane's element, grouping lanes by page.
+ *
+ * Hit pass (all groups at once): the lanes are grouped by page with ALU work
+ * only; every group leader pins its page with one fetch_add, all in the same
+ * instruction; groups whose page is RESIDENT access their elements, wait, and
+ * unpin.  No wave waits for anything while it holds these pins.
+ * Miss pass: groups whose page was not resident give their pin back and go
+ * through gpuvm_acquire one page at a time, so that a wave never holds more
+ * than one frame while it waits or allocates. */
 template <typename T, typename Op>
 __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write, Op op) {
     using namespace gpuvm_detail;
     const unsigned long long byte = elem * sizeof(T);
     const unsigned int page = (unsigned int)(byte >> vm.page_shift);              /* address split */
     const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
-    bool pending = true;
+    const unsigned int lane = __lane_id();
+
+    /* group the active lanes by page: leader_lane = lowest lane with my page */
+    unsigned int leader_lane = lane;
+    unsigned int n_groups = 0;
+    {
+        bool ungrouped = true;
+        for (;;) {
+            const unsigned long long todo = __builtin_amdgcn_ballot_w64(ungrouped);
+            if (todo == 0) break;
+            const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
+            const unsigned int group_page = __builtin_amdgcn_readlane(page, first);
+            if (ungrouped && page == group_page) { leader_lane = first; ungrouped = false; }
+            ++n_groups;
+        }
+    }
+    const bool is_leader = leader_lane == lane;
+
+    /* hit pass */
+    unsigned long long word = 0;
+    if (is_leader) word = a_add(vm.pte + page, 1ull);
+    {
+        const unsigned int lo = __shfl((unsigned int)word, (int)leader_lane, 64);
+        const unsigned int hi = __shfl((unsigned int)(word >> 32), (int)leader_lane, 64);
+        word = ((unsigned long long)hi << 32) | lo;
+    }
+    const bool resident = ((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
+    if (resident)
+        op(reinterpret_cast<T *>(vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off));
+    wait_vm();
+    if (is_leader) {
+        if (resident) {
+            unsigned long long need = 0;
+            if (write && !(word & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
+            if (vm.policy == GPUVM_POLICY_CLOCK && !(word & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
+            if (need) a_or(vm.pte + page, need);
+        }
+        a_add(vm.pte + page, ~0ull);                          /* unpin, or give the pin back */
+    }
+    if (vm.flags & GPUVM_F_ACCESS_STATS) {
+        const unsigned long long active = __builtin_amdgcn_ballot_w64(true);
+        const unsigned long long hit_groups = __builtin_amdgcn_ballot_w64(is_leader && resident);
+        if (wave_now().leader) {
+            stat_add(vm, GPUVM_S_GROUPS, n_groups);
+            stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(active) - n_groups);
+            stat_add(vm, GPUVM_S_HITS, (unsigned long long)__popcll(hit_groups));
+        }
+    }
+
+    /* miss pass: one page at a time */
+    bool pending = !resident;
     for (;;) {
         const unsigned long long todo = __builtin_amdgcn_ballot_w64(pending);
         if (todo == 0) break;
         const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
         const unsigned int group_page = __builtin_amdgcn_readlane(page, first);
-        const bool mine = pending && page == group_page;
-        if (vm.flags & GPUVM_F_ACCESS_STATS) {
-            const unsigned long long members = __builtin_amdgcn_ballot_w64(mine);
-            if (wave_now().leader) {
-                stat_add(vm, GPUVM_S_GROUPS, 1);
-                stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(members) - 1);
-            }
-        }
         char *frame = gpuvm_acquire(vm, group_page, write);
-        if (mine) {
+        if (pending && page == group_page) {
             op(reinterpret_cast<T *>(frame + off));
             pending = false;
         }

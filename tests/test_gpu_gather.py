@@ -47,6 +47,8 @@ def test_gather_matches_oracle(gpu, policy, n_elems, page, frames, n_idx):
             assert st["faults"] == distinct and st["evictions"] == 0
         # dedup bookkeeping: every lane is either a group of its own or rides on one
         assert st["wave_page_groups"] + st["lanes_coalesced"] == n_idx
+        # every group either found its page resident (at once or after waiting) or faulted
+        assert st["hits"] + st["faults"] == st["wave_page_groups"]
         # a second run on the warm pool gives the same answer
         got2, _ = run_gather(b, idx)
         assert np.array_equal(got2, want)
@@ -86,7 +88,7 @@ def test_gather_full_size_config(gpu):
         assert got_sum == want_sum
         st, *_ = check_invariants(b, read_only=True, pristine=data)
         # independent-reference model: steady hit ratio ~ frames/pages = 1/4
-        assert 0.6 * n_idx < st["faults"] <= n_idx
+        assert 0.4 * n_idx < st["faults"] <= n_idx   # sanity band: ~3/4 miss minus in-flight coalescing across waves
         gv.gpuvm_reset(b.vm)
         st0 = gv.gpuvm_stats(b.vm)
         assert st0["faults"] == 0
@@ -119,3 +121,33 @@ def test_errors_are_reported_not_fatal(gpu):
         with pytest.raises(gv.GpuvmError) as e:
             gv.gpuvm_run_gather(b.vm, d_idx, 2, d_out, None)
         assert e.value.code == gv.EDEADLK
+
+
+def test_bounded_waits_drain_and_report(gpu):
+    """Failure handling forced from the host: with a spin limit of 1 a wave that
+    has to wait for another wave's fault gives up at once, records
+    GPUVM_EDEADLK and every kernel still runs to its end; after a reset the
+    handle works again."""
+    n_elems, page = 1 << 18, 4096
+    data = inputs.u32_values(8, 0, n_elems)
+    # many waves, few pages, small pool: pages are constantly LOADING / EVICTING
+    idx = ((np.arange(1 << 16) * 1024) % n_elems).astype(np.uint32)
+    want, _ = oracle.gather(data, idx)
+    with Backing(data, page, 16 * page) as b:
+        gv.gpuvm_configure(b.vm, 1, True)
+        d_idx, d_out = dev(idx), torch.zeros(idx.size, dtype=torch.int32, device="cuda")
+        gv.gpuvm_run_gather(b.vm, d_idx, idx.size, d_out, None)
+        torch.cuda.synchronize()                                  # the kernel drained
+        st_err = None
+        try:
+            gv.gpuvm_check(b.vm)
+        except gv.GpuvmError as e:
+            st_err = e.code
+        assert st_err in (None, gv.EDEADLK)
+        if st_err is None:                                        # nobody had to wait: result must be right
+            assert np.array_equal(host(d_out, np.uint32), want)
+        gv.gpuvm_reset(b.vm)
+        gv.gpuvm_configure(b.vm, 0, False)
+        got, _ = run_gather(b, idx)
+        assert np.array_equal(got, want)
+        check_invariants(b, read_only=True, pristine=data)
