@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
+    ap.add_argument("--sweep", default=None, choices=["oversubscription", "page_size"],
+                    help="instead of the benchmark line: one JSON line per point of a sweep")
     return ap.parse_args()
 
 
@@ -417,6 +419,140 @@ WORKLOADS = {"gather": GatherWorkload, "stream": StreamWorkload, "bfs": BfsWorkl
 DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "embedding": (2, 1), "scatter": (1, 0)}
 
 
+def timed_ms(torch, fn, reps=3):
+    best = float("inf")
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        e0, e1 = ev_pair(torch)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    return best
+
+
+def sweep_oversubscription(gv, torch, np, inputs, oracle):
+    """Slow-down against memory pressure, level = data / pool - 1 (paper:
+    Oversubscription Analysis), levels 0..11, both policies, for the random
+    gather (64 MiB, 4 KiB pages) and the edge-balanced BFS (R-MAT scale 24,
+    1 GiB of col_idx, 64 KiB pages).  Every point is checked against the oracle."""
+    levels = [0, 0.25, 0.5, 1, 2, 3, 5, 7, 9, 11]
+    n_elems, n_idx, page = 1 << 24, 1 << 20, 4096
+    data = inputs.u32_values(0x9E3779B9, 0, n_elems)
+    idx = inputs.u32_indices(1, 0, n_idx, n_elems)
+    want, _ = oracle.gather(data, idx)
+    arr = gv.pinned_array(data.shape, data.dtype)
+    arr[...] = data
+    d_idx = torch.from_numpy(idx.view(np.int32)).cuda()
+    d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
+    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO)):
+        base = None
+        for lv in levels:
+            pool = int(arr.nbytes / (lv + 1)) // page * page
+            vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, pool, pol)
+
+            def run():
+                gv.gpuvm_reset(vm)
+                gv.gpuvm_run_gather(vm, d_idx, n_idx, d_out, None)
+            ms = timed_ms(torch, run)
+            gv.gpuvm_check(vm)
+            st = gv.gpuvm_stats(vm)
+            ok = bool(np.array_equal(d_out.cpu().numpy().view(np.uint32), want))
+            base = base or ms
+            print(json.dumps({"sweep": "oversubscription", "workload": "random_gather_64MiB_4KiB_pages", "policy": pol_name,
+                              "level": lv, "pool_bytes": pool, "ms": round(ms, 3), "slowdown_vs_level0": round(ms / base, 3),
+                              "faults": st["faults"], "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "parity": ok}), flush=True)
+            gv.gpuvm_destroy(vm)
+    gv.free_pinned(arr)
+    scale, page = 24, 65536
+    d_rp, d_ci = inputs.t_rmat_csr(3, scale, "cuda")
+    carr = gv.pinned_array((d_ci.numel(),), np.int32)
+    torch.from_numpy(carr).copy_(d_ci)
+    del d_ci
+    torch.cuda.synchronize()
+    nv = 1 << scale
+    want = oracle.bfs(d_rp.cpu().numpy(), carr, 0)
+    d_level = torch.zeros(nv, dtype=torch.int32, device="cuda")
+    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO)):
+        base = None
+        for lv in levels:
+            pool = int(carr.nbytes / (lv + 1)) // page * page
+            vm = gv.gpuvm_create(carr.ctypes.data, carr.nbytes, page, pool, pol)
+
+            def run():
+                gv.gpuvm_reset(vm)
+                gv.gpuvm_run_bfs_balanced(vm, d_rp, nv, 0, d_level)
+            ms = timed_ms(torch, run)
+            st = gv.gpuvm_stats(vm)
+            ok = bool(np.array_equal(d_level.cpu().numpy(), want))
+            base = base or ms
+            print(json.dumps({"sweep": "oversubscription", "workload": "bfs_balanced_rmat24_64KiB_pages", "policy": pol_name,
+                              "level": lv, "pool_bytes": pool, "ms": round(ms, 3), "slowdown_vs_level0": round(ms / base, 3),
+                              "faults": st["faults"], "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "parity": ok}), flush=True)
+            gv.gpuvm_destroy(vm)
+    gv.free_pinned(carr)
+
+
+def sweep_page_size(gv, torch, np, inputs, oracle):
+    """Fault throughput against page size, 4 KiB .. 1 MiB (the paper's transfer
+    benchmark, Comparison with GPUDirect RDMA: one page per warp, flat from 4 KiB
+    up), on a cyclic streaming read (2 GiB fp32, pool 512 MiB, 2 passes: every
+    page access faults) and on the random gather (64 MiB)."""
+    n_floats, passes = 1 << 29, 2
+    arr = gv.pinned_array((n_floats,), np.float32)
+    ht = torch.from_numpy(arr)
+    for lo in range(0, n_floats, 1 << 26):
+        ht[lo:lo + (1 << 26)].copy_(inputs.t_f32_uniform(7, lo, 1 << 26, "cuda"))
+    torch.cuda.synchronize()
+    block = 1 << 18
+    sample = np.linspace(0, n_floats // block - 1, 32).astype(np.int64)
+    want = np.array([oracle.stream_reduce(arr[b * block:(b + 1) * block], block, 1)[0, 0] for b in sample])
+    scale = np.array([oracle.stream_abs(arr[b * block:(b + 1) * block], block)[0] for b in sample])
+    d_s = torch.zeros(n_floats // block, dtype=torch.float64, device="cuda")
+    for shift in range(12, 21):
+        page = 1 << shift
+        vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, 512 << 20, gv.POLICY_CLOCK)
+
+        def run():
+            gv.gpuvm_reset(vm)
+            for _ in range(passes):
+                gv.gpuvm_run_stream_reduce(vm, block, d_s)
+        ms = timed_ms(torch, run)
+        gv.gpuvm_check(vm)
+        st = gv.gpuvm_stats(vm)
+        ok = bool(np.all(np.abs(d_s.cpu().numpy()[sample] - want) <= 1e-5 * scale))
+        print(json.dumps({"sweep": "page_size", "workload": "stream_2GiB_pool_512MiB_2_passes", "page_bytes": page,
+                          "ms": round(ms, 3), "faults": st["faults"], "faults_per_s": round(st["faults"] / ms * 1e3),
+                          "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "waves": gv.gpuvm_max_waves(vm), "parity": ok}), flush=True)
+        gv.gpuvm_destroy(vm)
+    gv.free_pinned(arr)
+    n_elems, n_idx = 1 << 24, 1 << 20
+    data = inputs.u32_values(0x9E3779B9, 0, n_elems)
+    idx = inputs.u32_indices(1, 0, n_idx, n_elems)
+    want, _ = oracle.gather(data, idx)
+    garr = gv.pinned_array(data.shape, data.dtype)
+    garr[...] = data
+    d_idx = torch.from_numpy(idx.view(np.int32)).cuda()
+    d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
+    for shift in range(12, 19):
+        page = 1 << shift
+        vm = gv.gpuvm_create(garr.ctypes.data, garr.nbytes, page, 16 << 20, gv.POLICY_CLOCK)
+
+        def run():
+            gv.gpuvm_reset(vm)
+            gv.gpuvm_run_gather(vm, d_idx, n_idx, d_out, None)
+        ms = timed_ms(torch, run)
+        gv.gpuvm_check(vm)
+        st = gv.gpuvm_stats(vm)
+        ok = bool(np.array_equal(d_out.cpu().numpy().view(np.uint32), want))
+        print(json.dumps({"sweep": "page_size", "workload": "random_gather_64MiB_pool_16MiB", "page_bytes": page,
+                          "ms": round(ms, 3), "faults": st["faults"], "faults_per_s": round(st["faults"] / ms * 1e3),
+                          "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "waves": gv.gpuvm_max_waves(vm), "parity": ok}), flush=True)
+        gv.gpuvm_destroy(vm)
+    gv.free_pinned(garr)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -432,6 +568,10 @@ def main():
     torch.cuda.set_device(0)
     policy = gv.POLICY_CLOCK if args.policy == "clock" else gv.POLICY_FIFO
 
+    if args.sweep:
+        import oracle
+        (sweep_oversubscription if args.sweep == "oversubscription" else sweep_page_size)(gv, torch, np, inputs, oracle)
+        return
     link = measure_link(gv, torch, np)
     link_peak = max(link["wave_read_4k"], link["wave_read_64k"], link["wave_copy_4k"], link["hipMemcpy_h2d"])
 
