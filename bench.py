@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "embedding", "scatter"])
+    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "embedding", "scatter"])
     ap.add_argument("--policy", default="clock", choices=["clock", "fifo"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -297,6 +297,65 @@ class BfsWorkload:
         return {"vertices": self.nv, "edges": int(self.arr.size), "levels": self.levels}
 
 
+class CcWorkload(BfsWorkload):
+    """Weakly connected components (label propagation, edge-balanced) on the BFS graph."""
+    kernel = "k_cc_round_balanced"
+
+    def __init__(self, gv, torch, np, inputs, policy, scale=None):
+        super().__init__(gv, torch, np, inputs, policy, scale)
+        self.name = self.name.replace("bfs_", "cc_")
+
+    def launch(self):
+        self.levels = self.gv.gpuvm_run_cc_balanced(self.vm, self.d_rp, self.nv, self.d_level)
+
+    def verify(self, oracle):
+        np = self.np
+        self._rp = self.d_rp.cpu().numpy()
+        want = oracle.cc(self._rp, self.arr)
+        self.useful_bytes = int(self.arr.nbytes) * self.levels          # every round reads every edge
+        return bool(np.array_equal(self.d_level.cpu().numpy(), want))
+
+    def cpu_baseline(self, oracle):
+        t0 = time.perf_counter()
+        oracle.cc(self._rp, self.arr)
+        return time.perf_counter() - t0, "whole workload (label propagation to the fixed point)"
+
+
+class SsspWorkload(BfsWorkload):
+    """SSSP from vertex 0 on the BFS graph; col_idx and the uint32 weights (1..64)
+    are both paged from host, each with a pool of 25 % of its size."""
+    kernel = "k_sssp_round_balanced"
+
+    def __init__(self, gv, torch, np, inputs, policy, scale=None):
+        super().__init__(gv, torch, np, inputs, policy, scale)
+        self.name = self.name.replace("bfs_", "sssp_") + "_weights_paged"
+        n = self.arr.size
+        self.warr = gv.pinned_array((n,), np.uint32)
+        hw = torch.from_numpy(self.warr.view(np.int32))
+        for lo in range(0, n, 1 << 26):
+            k = min(1 << 26, n - lo)
+            hw[lo:lo + k].copy_(inputs.t_edge_weights(4, lo, k, "cuda"))
+        torch.cuda.synchronize()
+        self.vmw = gv.gpuvm_create(self.warr.ctypes.data, self.warr.nbytes, self.page, self.pool, policy)
+
+    def launch(self):
+        self.gv.gpuvm_reset(self.vmw)
+        self.levels = self.gv.gpuvm_run_sssp_balanced(self.vm, self.vmw, self.d_rp, self.nv, 0, self.d_level)
+        self.stats_w = self.gv.gpuvm_stats(self.vmw)
+
+    def verify(self, oracle):
+        np = self.np
+        self._rp = self.d_rp.cpu().numpy()
+        want = oracle.sssp(self._rp, self.arr, self.warr, 0)
+        self.useful_bytes = None
+        return bool(np.array_equal(self.d_level.cpu().numpy().view(np.uint32), want))
+
+    def cpu_baseline(self, oracle):
+        t0 = time.perf_counter()
+        oracle.sssp(self._rp, self.arr, self.warr, 0)
+        return time.perf_counter() - t0, "whole workload (Bellman-Ford sweeps to the fixed point)"
+
+
 class EmbeddingWorkload:
     """Embedding-bag lookup: 5e7 x 128 fp32 table (25.6 GB) in host memory, 64 KiB
     pages, 6.4 GB pool, 20 batches of 65536 bags x 32 Zipf(1.05) ids, sum pooling."""
@@ -414,9 +473,9 @@ class ScatterWorkload:
         return {"elements": self.n_elems, "updates": self.n_upd}
 
 
-WORKLOADS = {"gather": GatherWorkload, "stream": StreamWorkload, "bfs": BfsWorkload,
+WORKLOADS = {"gather": GatherWorkload, "stream": StreamWorkload, "bfs": BfsWorkload, "cc": CcWorkload, "sssp": SsspWorkload,
              "embedding": EmbeddingWorkload, "scatter": ScatterWorkload}
-DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "embedding": (2, 1), "scatter": (1, 0)}
+DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "embedding": (2, 1), "scatter": (1, 0)}
 
 
 def timed_ms(torch, fn, reps=3):
@@ -609,6 +668,9 @@ def main():
     wall = time.perf_counter() - t0
     gv.gpuvm_check(W.vm)
     st = gv.gpuvm_stats(W.vm)                        # counters of the last step (reset clears them)
+    if hasattr(W, "stats_w"):                        # second paged array (edge weights): add its traffic
+        for k in ("faults", "evictions", "bytes_in", "bytes_out"):
+            st[k] += W.stats_w[k]
     kern_s = sum(e0.elapsed_time(e1) for e0, e1 in events) * 1e-3 / len(events)
     step_s = wall / args.steps
 
@@ -629,8 +691,8 @@ def main():
         "faults_per_s": round(st["faults"] / step_s, 1),
         "faults_per_step": st["faults"],
         "evictions_per_step": st["evictions"],
-        "useful_GBps": round(W.useful_bytes / step_s / 1e9, 4),
-        "io_amplification": round(st["bytes_in"] / W.useful_bytes, 2),
+        "useful_GBps": round(W.useful_bytes / step_s / 1e9, 4) if W.useful_bytes else None,
+        "io_amplification": round(st["bytes_in"] / W.useful_bytes, 2) if W.useful_bytes else None,
         "frac_of_host_link": round(st["bytes_in"] / step_s / 1e9 / link_peak, 4),
         "link_out_GBps": round(st["bytes_out"] / step_s / 1e9, 3),
         "host_link_measured_GBps": link,

@@ -200,6 +200,25 @@ GPUVM_API int gpuvm_run_bfs_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int6
                                      int64_t src, int32_t *d_level, int *n_levels_out,
                                      void *stream);
 
+/* Weakly connected components on the same paged CSR graph, edge-balanced like
+ * gpuvm_run_bfs_balanced (paper: Graph Workloads evaluates BFS, CC and SSSP):
+ * label propagation until nothing changes; every round reads every edge.
+ * d_label[nv] (int32 out) = smallest vertex id of the vertex's component.
+ * *n_rounds_out (host, may be NULL) = rounds run.  Synchronises per round. */
+GPUVM_API int gpuvm_run_cc_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv,
+                                    int32_t *d_label, int *n_rounds_out, void *stream);
+
+/* Single-source shortest paths with uint32 edge weights that are paged from
+ * host memory as a second data set (paper: SSSP pages edges + weights):
+ * vm_weights is a handle over a uint32 array parallel to col_idx (same byte
+ * size and page size as vm, its own frame pool).  A wave holds one page of
+ * each handle at a time.  d_dist[nv] (uint32 out) = distance from src,
+ * 0xFFFFFFFF if unreachable; path lengths must stay below 2^32 - 1.
+ * Frontier-based Bellman-Ford rounds; synchronises per round. */
+GPUVM_API int gpuvm_run_sssp_balanced(gpuvm_t *vm, gpuvm_t *vm_weights, const int64_t *d_row_ptr,
+                                      int64_t nv, int64_t src, uint32_t *d_dist,
+                                      int *n_rounds_out, void *stream);
+
 /* Embedding-bag lookup with sum pooling over an fp32 table of `dim` columns
  * (dim * 4 bytes must divide page_bytes; dim a multiple of 64 up to 256):
  * d_out[bag][c] = sum_j table[d_ids[bag][j]][c], rows added in listed order in
@@ -207,6 +226,20 @@ GPUVM_API int gpuvm_run_bfs_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int6
 GPUVM_API int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids,
                                       size_t bags, size_t bag_len, float *d_out,
                                       void *stream);
+
+/* y = A^T x over a paged row-major fp32 matrix A[rows][cols] (rows * cols * 4
+ * = bytes): one thread per column walking down the rows - the column-order
+ * access of the paper's transfer-bound applications (MVT / ATAX pattern).
+ * d_x[rows] fp32, d_y[cols] fp64 out (fp64 accumulation, rows ascending). */
+GPUVM_API int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x,
+                                 double *d_y, void *stream);
+
+/* Filter-then-gather over two paged uint32 columns of equal length (paper:
+ * Query Evaluation Benchmarks - scan one column, fetch another only for the
+ * rows that pass): *d_count = #{i : key[i] > threshold}, *d_sum = sum of
+ * val[i] over those rows (both one uint64 in device memory, overwritten). */
+GPUVM_API int gpuvm_run_filter_sum(gpuvm_t *vm_key, gpuvm_t *vm_val, uint32_t threshold,
+                                   uint64_t *d_count, uint64_t *d_sum, void *stream);
 
 /* Scatter-increment over a uint64 data set: data[idx[k]] += 1 (device atomics
  * on the frame; pages become DIRTY and reach host_buf at eviction or flush). */

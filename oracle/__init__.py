@@ -4,8 +4,8 @@ Thin ctypes wrapper over ``gpuvm_oracle.c`` (plain sequential C, built with
 gcc).  Nothing here may be imported by the product package; only ``tests/``,
 ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg use it.
 
-Part 1 (``gather``, ``stream_reduce``, ``bfs``, ``embedding_bag``,
-``scatter_increment``): each workload computed directly on ordinary memory --
+Part 1 (``gather``, ``stream_reduce``, ``bfs``, ``cc``, ``sssp``,
+``embedding_bag``, ``scatter_increment``): each workload computed directly on ordinary memory --
 the definition of the result, since GPUVM's paging is transparent to the
 application (paper, System Overview, vector-addition listing).
 
@@ -52,10 +52,16 @@ def lib():
         L.oracle_stream_abs.argtypes = [vp, u64, u64, vp]
         L.oracle_bfs.argtypes = [vp, vp, i64, i64, vp]
         L.oracle_bfs.restype = C.c_int
+        L.oracle_cc.argtypes = [vp, vp, i64, vp]
+        L.oracle_cc.restype = C.c_int
+        L.oracle_sssp.argtypes = [vp, vp, vp, i64, i64, vp]
+        L.oracle_sssp.restype = C.c_int
         for f in (L.oracle_embedding_bag, L.oracle_embedding_bag_f32,
                   L.oracle_embedding_bag_abs):
             f.argtypes = [vp, u64, vp, u64, u64, vp]
         L.oracle_scatter_increment.argtypes = [vp, vp, u64]
+        L.oracle_matvec_t.argtypes = [vp, u64, u64, vp, vp, vp]
+        L.oracle_filter_sum.argtypes = [vp, vp, u64, C.c_uint32, vp, vp]
         L.sim_create.argtypes = [vp, u64, u64, u64, C.c_int]
         L.sim_create.restype = vp
         L.sim_destroy.argtypes = [vp]
@@ -124,6 +130,29 @@ def bfs(row_ptr, col_idx, src=0):
     return level
 
 
+def cc(row_ptr, col_idx):
+    """Smallest vertex id of each vertex's weakly connected component (int32)."""
+    row_ptr = _arr(row_ptr, np.int64)
+    col_idx = _arr(col_idx, np.int32)
+    nv = row_ptr.size - 1
+    assert row_ptr[-1] == col_idx.size
+    label = np.empty(nv, np.int32)
+    lib().oracle_cc(_p(row_ptr), _p(col_idx), nv, _p(label))
+    return label
+
+
+def sssp(row_ptr, col_idx, weight, src=0):
+    """Shortest-path distance from src with uint32 edge weights; 0xFFFFFFFF = unreachable."""
+    row_ptr = _arr(row_ptr, np.int64)
+    col_idx = _arr(col_idx, np.int32)
+    weight = _arr(weight, np.uint32)
+    nv = row_ptr.size - 1
+    assert 0 <= src < nv and row_ptr[-1] == col_idx.size == weight.size
+    dist = np.empty(nv, np.uint32)
+    lib().oracle_sssp(_p(row_ptr), _p(col_idx), _p(weight), nv, src, _p(dist))
+    return dist
+
+
 def _bag_args(table, ids):
     table = _arr(table, np.float32)
     ids = _arr(ids, np.int32)
@@ -165,6 +194,28 @@ def scatter_increment(host, idx):
     assert idx.size == 0 or int(idx.max()) < host.size
     lib().oracle_scatter_increment(_p(host), _p(idx), idx.size)
     return host
+
+
+def matvec_t(A, x):
+    """y = A^T x in double precision and sum_i |A[i][j] x[i]| per column."""
+    A = _arr(A, np.float32)
+    x = _arr(x, np.float32)
+    assert A.ndim == 2 and x.shape == (A.shape[0],)
+    y = np.empty(A.shape[1], np.float64)
+    yabs = np.empty(A.shape[1], np.float64)
+    lib().oracle_matvec_t(_p(A), A.shape[0], A.shape[1], _p(x), _p(y), _p(yabs))
+    return y, yabs
+
+
+def filter_sum(key, val, threshold):
+    """(#rows with key > threshold, sum of val over them)."""
+    key = _arr(key, np.uint32)
+    val = _arr(val, np.uint32)
+    assert key.shape == val.shape
+    c = np.zeros(1, np.uint64)
+    s = np.zeros(1, np.uint64)
+    lib().oracle_filter_sum(_p(key), _p(val), key.size, threshold, _p(c), _p(s))
+    return int(c[0]), int(s[0])
 
 
 # ---------------------------------------------------------------- Part 2

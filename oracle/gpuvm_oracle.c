@@ -114,6 +114,50 @@ int oracle_bfs(const int64_t *row_ptr, const int32_t *col_idx, int64_t nv,
     return 0;
 }
 
+/* Weakly connected components: label[v] = smallest vertex id in v's component
+ * when edge directions are ignored.  Plain label propagation to the fixed
+ * point: sweep all edges, pull both ends down to the smaller label, repeat
+ * until a sweep changes nothing.  Returns the number of sweeps. */
+int oracle_cc(const int64_t *row_ptr, const int32_t *col_idx, int64_t nv, int32_t *label)
+{
+    for (int64_t v = 0; v < nv; ++v) label[v] = (int32_t)v;
+    int sweeps = 0, changed = 1;
+    while (changed) {
+        changed = 0;
+        ++sweeps;
+        for (int64_t v = 0; v < nv; ++v)
+            for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+                int32_t u = col_idx[e];
+                if (label[v] < label[u]) { label[u] = label[v]; changed = 1; }
+                else if (label[u] < label[v]) { label[v] = label[u]; changed = 1; }
+            }
+    }
+    return sweeps;
+}
+
+/* Single-source shortest paths with non-negative integer weights, Bellman-Ford:
+ * relax every edge until a full sweep changes nothing.  dist[v] = 0xFFFFFFFF
+ * when v cannot be reached.  Returns the number of sweeps. */
+int oracle_sssp(const int64_t *row_ptr, const int32_t *col_idx, const uint32_t *weight,
+                int64_t nv, int64_t src, uint32_t *dist)
+{
+    for (int64_t v = 0; v < nv; ++v) dist[v] = 0xFFFFFFFFu;
+    dist[src] = 0;
+    int sweeps = 0, changed = 1;
+    while (changed) {
+        changed = 0;
+        ++sweeps;
+        for (int64_t v = 0; v < nv; ++v) {
+            if (dist[v] == 0xFFFFFFFFu) continue;
+            for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+                uint64_t nd = (uint64_t)dist[v] + weight[e];
+                if (nd < dist[col_idx[e]]) { dist[col_idx[e]] = (uint32_t)nd; changed = 1; }
+            }
+        }
+    }
+    return sweeps;
+}
+
 /* Embedding bag, sum pooling: out[bag][c] = sum_j table[ids[bag][j]][c].
  * Accumulated in double precision (the definition of the sum). */
 void oracle_embedding_bag(const float *table, uint64_t dim, const int32_t *ids,
@@ -155,6 +199,34 @@ void oracle_embedding_bag_abs(const float *table, uint64_t dim, const int32_t *i
             }
             out[b * dim + c] = acc;
         }
+}
+
+/* Transposed matrix-vector product: y[j] = sum_i A[i][j] * x[i], row-major A,
+ * double precision; yabs[j] = sum_i |A[i][j] * x[i]| (tolerance scale). */
+void oracle_matvec_t(const float *A, uint64_t rows, uint64_t cols, const float *x,
+                     double *y, double *yabs)
+{
+    for (uint64_t j = 0; j < cols; ++j) {
+        double acc = 0.0, aabs = 0.0;
+        for (uint64_t i = 0; i < rows; ++i) {
+            double t = (double)A[i * cols + j] * (double)x[i];
+            acc += t;
+            aabs += t < 0 ? -t : t;
+        }
+        y[j] = acc;
+        if (yabs) yabs[j] = aabs;
+    }
+}
+
+/* Filter then gather: count the rows with key > threshold and sum val over them. */
+void oracle_filter_sum(const uint32_t *key, const uint32_t *val, uint64_t n,
+                       uint32_t threshold, uint64_t *count, uint64_t *sum)
+{
+    uint64_t c = 0, s = 0;
+    for (uint64_t i = 0; i < n; ++i)
+        if (key[i] > threshold) { c += 1; s += val[i]; }
+    *count = c;
+    *sum = s;
 }
 
 /* Scatter-increment: host[idx[k]] += 1 for every k. */

@@ -78,7 +78,11 @@ _SIGNATURES = {
     "gpuvm_run_stream_reduce": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_bfs": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_bfs_balanced": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
+    "gpuvm_run_cc_balanced": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
+    "gpuvm_run_sssp_balanced": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_embedding_bag": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_run_matvec_t": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_run_filter_sum": ([C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_scatter_increment": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_gather_phased": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_scatter_increment_phased": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p], C.c_int),
@@ -224,8 +228,29 @@ def gpuvm_run_bfs_balanced(vm, d_row_ptr, nv, src, d_level, stream=None):
     return levels.value
 
 
+def gpuvm_run_cc_balanced(vm, d_row_ptr, nv, d_label, stream=None):
+    rounds = C.c_int(0)
+    _call("gpuvm_run_cc_balanced", vm, _ptr(d_row_ptr), nv, _ptr(d_label), C.byref(rounds), _stream(stream))
+    return rounds.value
+
+
+def gpuvm_run_sssp_balanced(vm, vm_weights, d_row_ptr, nv, src, d_dist, stream=None):
+    rounds = C.c_int(0)
+    _call("gpuvm_run_sssp_balanced", vm, vm_weights, _ptr(d_row_ptr), nv, src, _ptr(d_dist), C.byref(rounds),
+          _stream(stream))
+    return rounds.value
+
+
 def gpuvm_run_embedding_bag(vm, dim, d_ids, bags, bag_len, d_out, stream=None):
     _call("gpuvm_run_embedding_bag", vm, dim, _ptr(d_ids), bags, bag_len, _ptr(d_out), _stream(stream))
+
+
+def gpuvm_run_matvec_t(vm, rows, cols, d_x, d_y, stream=None):
+    _call("gpuvm_run_matvec_t", vm, rows, cols, _ptr(d_x), _ptr(d_y), _stream(stream))
+
+
+def gpuvm_run_filter_sum(vm_key, vm_val, threshold, d_count, d_sum, stream=None):
+    _call("gpuvm_run_filter_sum", vm_key, vm_val, threshold, _ptr(d_count), _ptr(d_sum), _stream(stream))
 
 
 def gpuvm_run_scatter_increment(vm, d_idx, n, stream=None):

@@ -110,6 +110,12 @@ def rmat_edges(seed, lo, n, scale, a=0.57, b=0.19, c=0.19):
     return src, dst
 
 
+def edge_weights(seed, lo, n, max_weight=64):
+    """uint32 edge weights in [1, max_weight] (max_weight a power of two), by edge position."""
+    assert max_weight & (max_weight - 1) == 0
+    return ((splitmix64(seed, _counter(lo, n)) >> np.uint64(40)) & np.uint64(max_weight - 1)).astype(np.uint32) + np.uint32(1)
+
+
 def csr_from_edges(src, dst, n_vertices, scale):
     """CSR of a directed edge list: rows by source, each row's neighbours in
     ascending order (sort of the combined key), duplicates kept."""
@@ -178,6 +184,11 @@ def t_f32_uniform(seed, lo, n, device):
     import torch
     k = _lsr(t_splitmix64(seed, _t_counter(lo, n, device)), 40)
     return (k - (1 << 23)).to(torch.float32) * (2.0 ** -23)
+
+
+def t_edge_weights(seed, lo, n, device, max_weight=64):
+    import torch
+    return ((_lsr(t_splitmix64(seed, _t_counter(lo, n, device)), 40) & (max_weight - 1)) + 1).to(torch.int32)
 
 
 def t_rmat_edges(seed, lo, n, scale, device, a=0.57, b=0.19, c=0.19):

@@ -182,3 +182,87 @@ def test_store_then_load_roundtrip_through_eviction(gpu):
         assert np.array_equal(b.arr, want)
         st = gv.gpuvm_stats(b.vm)
         assert st["writebacks_evict"] > 10 * frames
+
+
+# ---------------------------------------------------------------- CC and SSSP (edge-balanced)
+
+@pytest.mark.parametrize("scale,ef,page,frames", [(14, 16, 4096, 16), (16, 2, 65536, 8), (12, 1, 4096, 256)])
+def test_cc_balanced(gpu, scale, ef, page, frames):
+    rp, ci = inputs.rmat_csr(7, scale, edge_factor=ef)
+    nv = 1 << scale
+    want = oracle.cc(rp, ci)
+    with Backing(ci, page, frames * page) as b:
+        d_label = torch.zeros(nv, dtype=torch.int32, device="cuda")
+        rounds = gv.gpuvm_run_cc_balanced(b.vm, dev(rp), nv, d_label)
+        assert rounds >= 2
+        assert np.array_equal(d_label.cpu().numpy(), want)
+        st, *_ = check_invariants(b, read_only=True, pristine=ci)
+        if b.n_pages > frames:                                   # every round re-reads every page
+            assert st["faults"] >= (rounds - 1) * (b.n_pages - frames)
+
+
+@pytest.mark.parametrize("scale,page,frames,src", [(14, 4096, 16, 0), (16, 65536, 8, 5), (12, 4096, 256, 0)])
+def test_sssp_balanced(gpu, scale, page, frames, src):
+    rp, ci = inputs.rmat_csr(9, scale)
+    w = inputs.edge_weights(4, 0, ci.size)
+    nv = 1 << scale
+    want = oracle.sssp(rp, ci, w, src)
+    with Backing(ci, page, frames * page) as b, Backing(w, page, frames * page) as bw:
+        d_dist = torch.zeros(nv, dtype=torch.int32, device="cuda")
+        rounds = gv.gpuvm_run_sssp_balanced(b.vm, bw.vm, dev(rp), nv, src, d_dist)
+        assert rounds >= 2
+        assert np.array_equal(host(d_dist, np.uint32), want)
+        st, *_ = check_invariants(b, read_only=True, pristine=ci)
+        stw, *_ = check_invariants(bw, read_only=True, pristine=w)
+        assert st["faults"] == stw["faults"]                      # the two arrays are walked in lock step
+        with pytest.raises(gv.GpuvmError):                         # mismatched second array
+            gv.gpuvm_run_sssp_balanced(b.vm, b.vm, dev(rp), nv, src, d_dist)
+
+
+# ---------------------------------------------------------------- column-order access, sparse filter
+
+@pytest.mark.parametrize("rows,cols,page,frames", [
+    (512, 4096, 4096, 64),            # a row = 4 pages; 2048 pages over 64 frames
+    (300, 1000, 4096, 16),            # ragged: columns not a multiple of 64, short last page
+    (64, 16384, 65536, 8),
+])
+def test_matvec_t_column_order(gpu, rows, cols, page, frames):
+    A = inputs.f32_uniform(3, 0, rows * cols).reshape(rows, cols)
+    x = inputs.f32_uniform(4, 0, rows)
+    want, scale = oracle.matvec_t(A, x)
+    with Backing(A, page, frames * page) as b:
+        d_y = torch.full((cols,), -1.0, dtype=torch.float64, device="cuda")
+        gv.gpuvm_run_matvec_t(b.vm, rows, cols, dev(x), d_y)
+        gv.gpuvm_check(b.vm)
+        got = d_y.cpu().numpy()
+        assert np.all(np.abs(got - want) <= 1e-5 * scale)          # stated bar
+        assert np.all(np.abs(got - want) <= 1e-12 * scale + 1e-300)  # same order, fp64: essentially exact
+        check_invariants(b, read_only=True, pristine=A)
+        with pytest.raises(gv.GpuvmError):
+            gv.gpuvm_run_matvec_t(b.vm, rows + 1, cols, dev(x), d_y)
+
+
+@pytest.mark.parametrize("n,page,frames,sel", [
+    (1 << 20, 4096, 32, 0.0008),      # the paper's 0.08 % selectivity, 4 KiB pages
+    ((1 << 18) + 333, 4096, 16, 0.02),
+    (1 << 16, 65536, 8, 0.5),
+])
+def test_filter_sum(gpu, n, page, frames, sel):
+    key = inputs.u32_values(5, 0, n)
+    val = inputs.u32_values(6, 0, n)
+    thr = 0xFFFFFFFF - int(sel * 2 ** 32)
+    want = oracle.filter_sum(key, val, thr)
+    with Backing(key, page, frames * page) as bk, Backing(val, page, frames * page) as bv:
+        d_c = torch.zeros(1, dtype=torch.int64, device="cuda")
+        d_s = torch.zeros(1, dtype=torch.int64, device="cuda")
+        for _ in range(2):
+            gv.gpuvm_run_filter_sum(bk.vm, bv.vm, thr, d_c, d_s)
+            gv.gpuvm_check(bk.vm)
+            gv.gpuvm_check(bv.vm)
+            assert (int(host(d_c, np.uint64)[0]), int(host(d_s, np.uint64)[0])) == want
+        stk, *_ = check_invariants(bk, read_only=True, pristine=key)
+        stv, *_ = check_invariants(bv, read_only=True, pristine=val)
+        touched = len(np.unique(np.nonzero(key > thr)[0] * 4 // page))
+        assert stv["faults"] >= touched                              # only pages with a matching row are fetched
+        if sel < 0.001:
+            assert stv["faults"] < 2 * bv.n_pages * 0.8             # well below two full scans

@@ -190,3 +190,82 @@ def test_torch_twins_match_numpy():
     rp, ci = inputs.rmat_csr(2, 9)
     trp, tci = inputs.t_rmat_csr(2, 9, "cpu", chunk=1000)
     assert np.array_equal(trp.numpy(), rp) and np.array_equal(tci.numpy(), ci)
+
+
+# ---------------------------------------------------------------- CC and SSSP
+
+def test_cc_against_scipy_and_special_cases():
+    from scipy.sparse.csgraph import connected_components
+    rp, ci = _csr(7, [(0, 1), (2, 1), (3, 4), (5, 5)])          # {0,1,2} {3,4} {5} {6}
+    assert oracle.cc(rp, ci).tolist() == [0, 0, 0, 3, 3, 5, 6]
+    rp, ci = _csr(6, [(5, 4), (4, 3), (3, 2), (2, 1), (1, 0)])  # a path against the sweep direction
+    assert oracle.cc(rp, ci).tolist() == [0] * 6
+    for scale, ef in ((9, 1), (10, 2), (11, 8)):
+        rp, ci = inputs.rmat_csr(7, scale, edge_factor=ef)
+        nv = 1 << scale
+        label = oracle.cc(rp, ci)
+        m = sp.csr_matrix((np.ones(ci.size, np.int8), ci.copy(), rp.copy()), shape=(nv, nv))
+        ncomp, comp = connected_components(m, directed=True, connection="weak")
+        assert len(np.unique(label)) == ncomp
+        # same partition, and the label is the smallest member
+        first = np.full(ncomp, nv, np.int64)
+        np.minimum.at(first, comp, np.arange(nv))
+        assert np.array_equal(label, first[comp].astype(np.int32))
+
+
+def test_sssp_against_scipy_and_special_cases():
+    from scipy.sparse.csgraph import dijkstra
+    INF = 0xFFFFFFFF
+    rp, ci = _csr(5, [(0, 1), (0, 2), (1, 2), (2, 3)])
+    w = np.array([10, 1, 1, 5], np.uint32)                       # edges sorted by source: 0->1, 0->2, 1->2, 2->3
+    assert oracle.sssp(rp, ci, w, 0).tolist() == [0, 10, 1, 6, INF]
+    assert oracle.sssp(rp, ci, w, 1).tolist() == [INF, 0, 1, 6, INF]
+    # unit weights: SSSP is BFS
+    rp, ci = inputs.rmat_csr(3, 10, edge_factor=8)
+    lv = oracle.bfs(rp, ci, 0)
+    d = oracle.sssp(rp, ci, np.ones(ci.size, np.uint32), 0)
+    assert np.array_equal(np.where(d == INF, -1, d).astype(np.int32), lv)
+    # random weights against scipy (duplicate edges: scipy needs the lightest one)
+    w = inputs.edge_weights(9, 0, ci.size)
+    assert w.min() >= 1 and w.max() <= 64
+    nv = rp.size - 1
+    src = np.repeat(np.arange(nv), np.diff(rp))
+    key = src.astype(np.int64) * nv + ci
+    order = np.lexsort((w, key))
+    keep = np.ones(ci.size, bool)
+    keep[1:] = key[order][1:] != key[order][:-1]
+    sel = order[keep]
+    m = sp.csr_matrix((w[sel].astype(np.float64), (src[sel], ci[sel])), shape=(nv, nv))
+    ref = dijkstra(m, directed=True, indices=0)
+    want = np.where(np.isinf(ref), INF, ref).astype(np.uint32)
+    assert np.array_equal(oracle.sssp(rp, ci, w, 0), want)
+
+
+# ---------------------------------------------------------------- column-order product, filter-then-gather
+
+def test_matvec_t_against_numpy_and_closed_form():
+    A = np.arange(12, dtype=np.float32).reshape(4, 3)            # columns 0 3 6 9 / 1 4 7 10 / 2 5 8 11
+    x = np.array([1, 10, 100, 1000], np.float32)
+    y, yabs = oracle.matvec_t(A, x)
+    assert y.tolist() == [9630.0, 10741.0, 11852.0] and yabs.tolist() == y.tolist()
+    A = inputs.f32_uniform(3, 0, 300 * 70).reshape(300, 70)
+    x = inputs.f32_uniform(4, 0, 300)
+    y, yabs = oracle.matvec_t(A, x)
+    ref = A.astype(np.float64).T @ x.astype(np.float64)
+    assert np.max(np.abs(y - ref)) <= 1e-12
+    assert np.all(yabs >= np.abs(y)) and np.allclose(yabs, np.abs(A.astype(np.float64) * x[:, None]).sum(0), rtol=1e-12)
+    yt, _ = oracle.matvec_t(np.ascontiguousarray(A.T), inputs.f32_uniform(4, 0, 70))   # not symmetric in rows/cols
+    assert yt.shape == (300,)
+
+
+def test_filter_sum_against_numpy():
+    key = inputs.u32_values(5, 0, 100000)
+    val = inputs.u32_values(6, 0, 100000)
+    thr = 0xFFFFFFFF - int(0.0008 * 2 ** 32)
+    c, s = oracle.filter_sum(key, val, thr)
+    m = key > thr
+    assert c == int(m.sum()) and 40 < c < 130                     # ~0.08 % of the rows
+    assert s == int(val[m].astype(np.uint64).sum())
+    assert oracle.filter_sum(key, val, 0xFFFFFFFF) == (0, 0)
+    assert oracle.filter_sum(key[:0], val[:0], 5) == (0, 0)
+    assert oracle.filter_sum(np.array([6, 5, 7], np.uint32), np.array([1, 2, 4], np.uint32), 5) == (2, 5)
