@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "embedding", "scatter"])
+    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "filter", "embedding", "scatter"])
     ap.add_argument("--policy", default="clock", choices=["clock", "fifo"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -356,6 +356,98 @@ class SsspWorkload(BfsWorkload):
         return time.perf_counter() - t0, "whole workload (Bellman-Ford sweeps to the fixed point)"
 
 
+class MatvecTWorkload:
+    """y = A^T x, A 32768 x 32768 fp32 (4 GiB) paged from host, one thread per
+    column (column-order access), 64 KiB pages, 1 GiB pool."""
+    rows, cols, page, pool = 32768, 32768, 65536, 1 << 30
+    dtype = "f64"
+    kernel = "k_matvec_t"
+    name = "matvec_t_32768x32768_f32_column_order_64KiB_pages_1GiB_pool"
+
+    def __init__(self, gv, torch, np, inputs, policy):
+        self.gv, self.torch, self.np = gv, torch, np
+        n = self.rows * self.cols
+        self.arr = gv.pinned_array((self.rows, self.cols), np.float32)
+        ht = torch.from_numpy(self.arr).view(-1)
+        for lo in range(0, n, 1 << 26):
+            ht[lo:lo + (1 << 26)].copy_(inputs.t_f32_uniform(3, lo, 1 << 26, "cuda"))
+        torch.cuda.synchronize()
+        self.x = inputs.f32_uniform(4, 0, self.rows)
+        self.d_x = torch.from_numpy(self.x).cuda()
+        self.d_y = torch.zeros(self.cols, dtype=torch.float64, device="cuda")
+        self.vm = gv.gpuvm_create(self.arr.ctypes.data, self.arr.nbytes, self.page, self.pool, policy)
+        self.useful_bytes = n * 4
+
+    def launch(self):
+        self.gv.gpuvm_run_matvec_t(self.vm, self.rows, self.cols, self.d_x, self.d_y)
+
+    def verify(self, oracle):
+        np = self.np
+        cols = np.linspace(0, self.cols - 64, 16).astype(np.int64)          # sampled column blocks
+        got = self.d_y.cpu().numpy()
+        ok = True
+        for c in cols:
+            want, scale = oracle.matvec_t(np.ascontiguousarray(self.arr[:, c:c + 64]), self.x)
+            ok &= bool(np.all(np.abs(got[c:c + 64] - want) <= 1e-5 * scale))
+        return ok
+
+    def cpu_baseline(self, oracle):
+        sub = self.np.ascontiguousarray(self.arr[:, :1024])
+        t0 = time.perf_counter()
+        oracle.matvec_t(sub, self.x)
+        return (time.perf_counter() - t0) * (self.cols / 1024), "1024 of the 32768 columns, scaled"
+
+    def config(self):
+        return {"rows": self.rows, "cols": self.cols}
+
+
+class FilterWorkload:
+    """Filter-then-gather over two uint32 columns of 2^28 rows (1 GiB each), 4 KiB
+    pages, 256 MiB pool per column, selectivity 0.08 %."""
+    n, page, pool, sel = 1 << 28, 4096, 256 << 20, 0.0008
+    dtype = "u32"
+    kernel = "k_filter_sum"
+    name = "filter_sum_2x1GiB_u32_columns_4KiB_pages_256MiB_pools_selectivity_0.08pct"
+
+    def __init__(self, gv, torch, np, inputs, policy):
+        self.gv, self.torch, self.np = gv, torch, np
+        self.arr = gv.pinned_array((self.n,), np.uint32)                    # key column
+        self.varr = gv.pinned_array((self.n,), np.uint32)
+        hk, hv = torch.from_numpy(self.arr.view(np.int32)), torch.from_numpy(self.varr.view(np.int32))
+        for lo in range(0, self.n, 1 << 26):
+            hk[lo:lo + (1 << 26)].copy_(inputs.t_u32_values(5, lo, 1 << 26, "cuda"))
+            hv[lo:lo + (1 << 26)].copy_(inputs.t_u32_values(6, lo, 1 << 26, "cuda"))
+        torch.cuda.synchronize()
+        self.thr = 0xFFFFFFFF - int(self.sel * 2 ** 32)
+        self.vm = gv.gpuvm_create(self.arr.ctypes.data, self.arr.nbytes, self.page, self.pool, policy)
+        self.vmw = gv.gpuvm_create(self.varr.ctypes.data, self.varr.nbytes, self.page, self.pool, policy)
+        self.d_c = torch.zeros(1, dtype=torch.int64, device="cuda")
+        self.d_s = torch.zeros(1, dtype=torch.int64, device="cuda")
+        self.useful_bytes = self.n * 4                                       # the scan itself; matches add 8 B each
+
+    def launch(self):
+        self.gv.gpuvm_reset(self.vmw)
+        self.gv.gpuvm_run_filter_sum(self.vm, self.vmw, self.thr, self.d_c, self.d_s)
+        self.gv.gpuvm_check(self.vmw)
+        self.stats_w = self.gv.gpuvm_stats(self.vmw)
+
+    def verify(self, oracle):
+        np = self.np
+        want = oracle.filter_sum(self.arr, self.varr, self.thr)
+        got = (int(self.d_c.cpu().numpy().view(np.uint64)[0]), int(self.d_s.cpu().numpy().view(np.uint64)[0]))
+        self.matches = want[0]
+        return got == want
+
+    def cpu_baseline(self, oracle):
+        t0 = time.perf_counter()
+        oracle.filter_sum(self.arr, self.varr, self.thr)
+        return time.perf_counter() - t0, "whole workload (2^28 rows)"
+
+    def config(self):
+        return {"rows": self.n, "selectivity": self.sel, "matches": getattr(self, "matches", None),
+                "value_column_faults": self.stats_w["faults"], "value_column_pages": self.n * 4 // self.page}
+
+
 class EmbeddingWorkload:
     """Embedding-bag lookup: 5e7 x 128 fp32 table (25.6 GB) in host memory, 64 KiB
     pages, 6.4 GB pool, 20 batches of 65536 bags x 32 Zipf(1.05) ids, sum pooling."""
@@ -474,8 +566,9 @@ class ScatterWorkload:
 
 
 WORKLOADS = {"gather": GatherWorkload, "stream": StreamWorkload, "bfs": BfsWorkload, "cc": CcWorkload, "sssp": SsspWorkload,
+             "matvec_t": MatvecTWorkload, "filter": FilterWorkload,
              "embedding": EmbeddingWorkload, "scatter": ScatterWorkload}
-DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "embedding": (2, 1), "scatter": (1, 0)}
+DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "matvec_t": (3, 1), "filter": (5, 1), "embedding": (2, 1), "scatter": (1, 0)}
 
 
 def timed_ms(torch, fn, reps=3):

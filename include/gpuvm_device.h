@@ -27,7 +27,8 @@
  *
  * Page-table word (one 64-bit atomic per page, all updates are atomics that
  * leave the pin count of concurrent users intact):
- *     bits  0..31  pin    reference counter: waves that use or wait for the page
+ *     bits  0..19  pin    reference counter: waves that use or wait for the page
+ *     bits 20..31  gen    install generation, +1 every time the page becomes RESIDENT
  *     bit   32     REF    CLOCK reference bit
  *     bit   33     DIRTY  frame differs from host memory
  *     bits 34..35  state  0 INVALID, 1 LOADING, 2 RESIDENT, 3 EVICTING
@@ -58,7 +59,11 @@
 #include <hip/hip_runtime.h>
 #include "gpuvm.h"
 
-#define GPUVM_PTE_PIN_MASK    0x00000000FFFFFFFFull
+#define GPUVM_PTE_PIN_MASK    0x00000000000FFFFFull
+#define GPUVM_PTE_GEN_SHIFT   20
+#define GPUVM_PTE_GEN_MASK    0x00000000FFF00000ull
+#define GPUVM_PTE_KEEP_MASK   (GPUVM_PTE_PIN_MASK | GPUVM_PTE_GEN_MASK)   /* survives INVALID */
+#define GPUVM_PTE_IDENT_MASK  (GPUVM_PTE_GEN_MASK | GPUVM_PTE_STATE_MASK | ~((1ull << GPUVM_PTE_FRAME_SHIFT) - 1))
 #define GPUVM_PTE_REF         (1ull << 32)
 #define GPUVM_PTE_DIRTY       (1ull << 33)
 #define GPUVM_PTE_STATE_SHIFT 34
@@ -212,7 +217,8 @@ GPUVM_DEV void copy_frame_to_host(char *host, const char *frame, unsigned int by
 /* Frame allocation + eviction + migration for `page`, whose state word this
  * wave has just moved INVALID -> LOADING.  Returns the frame, or GPUVM_NO_PAGE
  * if a bounded wait ran out (error recorded). */
-GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool write, const wave_t &w) {
+GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool write, unsigned int gen,
+                             const wave_t &w) {
     unsigned int f = 0, victim = GPUVM_NO_PAGE, wb = 0, ok = 1;
     if (w.leader) {
         unsigned long long skips = 0, sweeps = 0;
@@ -248,7 +254,7 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
     }
     ok = bcast(ok);
     if (!ok) {
-        if (w.leader) a_and(vm.pte + page, GPUVM_PTE_PIN_MASK);          /* back to INVALID */
+        if (w.leader) a_and(vm.pte + page, GPUVM_PTE_KEEP_MASK);         /* back to INVALID */
         return GPUVM_NO_PAGE;
     }
     f = bcast(f); victim = bcast(victim); wb = bcast(wb);
@@ -261,7 +267,7 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
             if (w.leader) { stat_add(vm, GPUVM_S_WB_EVICT, 1); stat_add(vm, GPUVM_S_BYTES_OUT, len); }
         }
         if (w.leader) {
-            a_and(vm.pte + victim, GPUVM_PTE_PIN_MASK);       /* INVALID; waiters keep their pins */
+            a_and(vm.pte + victim, GPUVM_PTE_KEEP_MASK);      /* INVALID; waiters keep their pins */
             stat_add(vm, GPUVM_S_EVICTIONS, 1);
         }
     }
@@ -270,10 +276,13 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
     if (w.leader) a_store(vm.frame_owner + f, page);
     wait_vm();                                                /* the page is in the frame */
     if (w.leader) {
+        /* only this wave changes anything but the pin field while the page is
+         * LOADING, so one xor moves state, frame, flags and generation at once */
         const unsigned long long flip =
             ((GPUVM_ST_LOADING ^ GPUVM_ST_RESIDENT) << GPUVM_PTE_STATE_SHIFT) |
             ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) | GPUVM_PTE_REF |
-            (write ? GPUVM_PTE_DIRTY : 0ull);
+            (write ? GPUVM_PTE_DIRTY : 0ull) |
+            ((unsigned long long)(gen ^ ((gen + 1u) & 0xFFFu)) << GPUVM_PTE_GEN_SHIFT);
         a_xor(vm.pte + page, flip);                           /* publish: RESIDENT */
         stat_add(vm, GPUVM_S_FAULTS, 1);
         stat_add(vm, GPUVM_S_BYTES_IN, len);
@@ -319,7 +328,7 @@ __device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned i
     if (how == 2) return vm.frames;
     unsigned int f;
     if (how == 1) {
-        f = fault(vm, page, write, w);
+        f = fault(vm, page, write, (unsigned int)(cur >> GPUVM_PTE_GEN_SHIFT) & 0xFFFu, w);
         if (f == GPUVM_NO_PAGE) return vm.frames;
     } else {
         cur = bcast(cur);
@@ -359,28 +368,41 @@ __device__ __forceinline__ gpuvm_detail::u32x4 gpuvm_frame_load_b128(const gpuvm
 }
 
 /* Element access with wavefront dedup: calls op(T*) once in every active lane
- * on the lane's element, grouping lanes by page.
+ * whose `want` is true, on the lane's element, grouping lanes by page.  Lanes
+ * with want == false take no element but help to move pages; calling this
+ * with all lanes of the wave active (and `want` as the predicate) is what
+ * keeps a fault one link round trip wide - under divergence only the active
+ * lanes can copy.
  *
  * Hit pass (all groups at once): the lanes are grouped by page with ALU work
- * only; every group leader pins its page with one fetch_add, all in the same
- * instruction; groups whose page is RESIDENT access their elements, wait, and
- * unpin.  No wave waits for anything while it holds these pins.
- * Miss pass: groups whose page was not resident give their pin back and go
- * through gpuvm_acquire one page at a time, so that a wave never holds more
- * than one frame while it waits or allocates. */
+ * only, then
+ *   - reads are optimistic: the leader loads the page's word, the lanes read
+ *     their elements from the frame it names, and the leader loads the word
+ *     again; if state, frame and install generation are unchanged the frame
+ *     held the page all the while (eviction changes the word before the frame
+ *     is reused, re-installation bumps the generation) and the values stand.
+ *     No atomic, no reference count: readers of a hot page do not serialise on
+ *     its word and never block its eviction;
+ *   - writes pin: every group leader takes a reference with one fetch_add, all
+ *     in the same instruction; resident groups update their elements, wait,
+ *     mark the page DIRTY and unpin.  No wave waits while it holds these pins.
+ * Miss pass: groups whose page was not resident (or whose optimistic read did
+ * not validate) go through gpuvm_acquire one page at a time, so that a wave
+ * never holds more than one frame while it waits or allocates. */
 template <typename T, typename Op>
-__device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write, Op op) {
+__device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write, bool want,
+                                             Op op) {
     using namespace gpuvm_detail;
     const unsigned long long byte = elem * sizeof(T);
     const unsigned int page = (unsigned int)(byte >> vm.page_shift);              /* address split */
     const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
     const unsigned int lane = __lane_id();
 
-    /* group the active lanes by page: leader_lane = lowest lane with my page */
+    /* group the wanting lanes by page: leader_lane = lowest lane with my page */
     unsigned int leader_lane = lane;
     unsigned int n_groups = 0;
     {
-        bool ungrouped = true;
+        bool ungrouped = want;
         for (;;) {
             const unsigned long long todo = __builtin_amdgcn_ballot_w64(ungrouped);
             if (todo == 0) break;
@@ -390,41 +412,58 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
             ++n_groups;
         }
     }
-    const bool is_leader = leader_lane == lane;
+    const bool is_leader = want && leader_lane == lane;
 
     /* hit pass */
     unsigned long long word = 0;
-    if (is_leader) word = a_add(vm.pte + page, 1ull);
+    if (is_leader) word = write ? a_add(vm.pte + page, 1ull) : a_load(vm.pte + page);
     {
         const unsigned int lo = __shfl((unsigned int)word, (int)leader_lane, 64);
         const unsigned int hi = __shfl((unsigned int)(word >> 32), (int)leader_lane, 64);
         word = ((unsigned long long)hi << 32) | lo;
     }
-    const bool resident = ((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
+    bool resident = want && ((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
     if (resident)
         op(reinterpret_cast<T *>(vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off));
     wait_vm();
-    if (is_leader) {
-        if (resident) {
-            unsigned long long need = 0;
-            if (write && !(word & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
-            if (vm.policy == GPUVM_POLICY_CLOCK && !(word & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
-            if (need) a_or(vm.pte + page, need);
+    if (write) {
+        if (is_leader) {
+            if (resident) {
+                unsigned long long need = 0;
+                if (!(word & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
+                if (vm.policy == GPUVM_POLICY_CLOCK && !(word & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
+                if (need) a_or(vm.pte + page, need);
+            }
+            a_add(vm.pte + page, ~0ull);                      /* unpin, or give the pin back */
         }
-        a_add(vm.pte + page, ~0ull);                          /* unpin, or give the pin back */
+    } else {
+        unsigned int still = 0;
+        if (is_leader && resident) {
+            const unsigned long long again = a_load(vm.pte + page);
+            still = ((again ^ word) & GPUVM_PTE_IDENT_MASK) == 0;
+            /* second-chance bit, best effort: a CAS, because without a pin the
+             * page may leave at any moment and a plain OR could then mark an
+             * entry that is no longer RESIDENT */
+            if (still && vm.policy == GPUVM_POLICY_CLOCK && !(again & GPUVM_PTE_REF)) {
+                unsigned long long expect = again;
+                a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
+            }
+        }
+        still = __shfl(still, (int)leader_lane, 64);
+        resident = resident && still != 0;                    /* else: redo through the pinned path */
     }
     if (vm.flags & GPUVM_F_ACCESS_STATS) {
-        const unsigned long long active = __builtin_amdgcn_ballot_w64(true);
+        const unsigned long long wanting = __builtin_amdgcn_ballot_w64(want);
         const unsigned long long hit_groups = __builtin_amdgcn_ballot_w64(is_leader && resident);
         if (wave_now().leader) {
             stat_add(vm, GPUVM_S_GROUPS, n_groups);
-            stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(active) - n_groups);
+            stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(wanting) - n_groups);
             stat_add(vm, GPUVM_S_HITS, (unsigned long long)__popcll(hit_groups));
         }
     }
 
     /* miss pass: one page at a time */
-    bool pending = !resident;
+    bool pending = want && !resident;
     for (;;) {
         const unsigned long long todo = __builtin_amdgcn_ballot_w64(pending);
         if (todo == 0) break;
@@ -441,31 +480,44 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
 
 /* Elements are 4 or 8 bytes wide and are read, written and updated with
  * relaxed agent-scope atomics, which is what keeps frame data coherent
- * between the XCDs without cache maintenance. */
+ * between the XCDs without cache maintenance.  The *_if forms take the lane's
+ * predicate and are meant to be called by all lanes of the wave together. */
 template <typename T>
-__device__ __forceinline__ T gpuvm_load(const gpuvm_dev_t &vm, unsigned long long elem) {
+__device__ __forceinline__ T gpuvm_load_if(const gpuvm_dev_t &vm, unsigned long long elem, bool want) {
     static_assert(sizeof(T) == 4 || sizeof(T) == 8, "gpuvm_load: 4- or 8-byte elements");
     T v{};
-    gpuvm_access<T>(vm, elem, false, [&](T *p) {
+    gpuvm_access<T>(vm, elem, false, want, [&](T *p) {
         v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     });
     return v;
 }
+template <typename T>
+__device__ __forceinline__ T gpuvm_load(const gpuvm_dev_t &vm, unsigned long long elem) {
+    return gpuvm_load_if<T>(vm, elem, true);
+}
 
 template <typename T>
-__device__ __forceinline__ void gpuvm_store(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
+__device__ __forceinline__ void gpuvm_store_if(const gpuvm_dev_t &vm, unsigned long long elem, T v, bool want) {
     static_assert(sizeof(T) == 4 || sizeof(T) == 8, "gpuvm_store: 4- or 8-byte elements");
-    gpuvm_access<T>(vm, elem, true, [&](T *p) {
+    gpuvm_access<T>(vm, elem, true, want, [&](T *p) {
         __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     });
+}
+template <typename T>
+__device__ __forceinline__ void gpuvm_store(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
+    gpuvm_store_if<T>(vm, elem, v, true);
 }
 
 /* data[elem] += v with a device-scope atomic on the frame; returns nothing. */
 template <typename T>
-__device__ __forceinline__ void gpuvm_atomic_add(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
-    gpuvm_access<T>(vm, elem, true, [&](T *p) {
+__device__ __forceinline__ void gpuvm_atomic_add_if(const gpuvm_dev_t &vm, unsigned long long elem, T v, bool want) {
+    gpuvm_access<T>(vm, elem, true, want, [&](T *p) {
         __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     });
+}
+template <typename T>
+__device__ __forceinline__ void gpuvm_atomic_add(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
+    gpuvm_atomic_add_if<T>(vm, elem, v, true);
 }
 
 #endif /* GPUVM_DEVICE_H */

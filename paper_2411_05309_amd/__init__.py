@@ -24,7 +24,9 @@ STAT_NAMES = ("faults", "evictions", "writebacks_evict", "writebacks_flush",
               "phases")
 
 # page-table word layout (include/gpuvm_device.h)
-PTE_PIN_MASK = 0xFFFFFFFF
+PTE_PIN_MASK = 0xFFFFF
+PTE_GEN_SHIFT = 20
+PTE_GEN_MASK = 0xFFF00000
 PTE_REF = 1 << 32
 PTE_DIRTY = 1 << 33
 PTE_STATE_SHIFT = 34
@@ -305,6 +307,7 @@ def decode_pte(pte):
     import numpy as np
     pte = np.asarray(pte, np.uint64)
     return dict(pin=(pte & np.uint64(PTE_PIN_MASK)).astype(np.int64),
+                gen=((pte & np.uint64(PTE_GEN_MASK)) >> np.uint64(PTE_GEN_SHIFT)).astype(np.int64),
                 ref=((pte >> np.uint64(32)) & np.uint64(1)).astype(np.uint8),
                 dirty=((pte >> np.uint64(33)) & np.uint64(1)).astype(np.uint8),
                 state=((pte >> np.uint64(PTE_STATE_SHIFT)) & np.uint64(3)).astype(np.uint8),

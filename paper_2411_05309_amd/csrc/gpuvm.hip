@@ -107,12 +107,13 @@ __global__ __launch_bounds__(kBlock) void k_gather(gpuvm_dev_t vm, const uint32_
                                                     unsigned long long n_elems) {
     const size_t nthreads = (size_t)gridDim.x * kBlock;
     unsigned long long acc = 0;
-    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n; k += nthreads) {
-        unsigned long long i = idx[k];
-        if (i >= n_elems) { raise_error(vm, GPUVM_ERANGE); continue; }
-        const uint32_t v = gpuvm_load<uint32_t>(vm, i);
-        out[k] = v;
-        acc += v;
+    const size_t n_up = (n + 63) & ~(size_t)63;                  // whole waves iterate together
+    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n_up; k += nthreads) {
+        unsigned long long i = k < n ? idx[k] : 0;
+        bool want = k < n;
+        if (want && i >= n_elems) { raise_error(vm, GPUVM_ERANGE); want = false; }
+        const uint32_t v = gpuvm_load_if<uint32_t>(vm, i, want);
+        if (want) { out[k] = v; acc += v; }
     }
     if (sum) {
         // every lane of the wave reaches this point (the loop has ended for all)
@@ -126,10 +127,12 @@ __global__ __launch_bounds__(kBlock) void k_gather(gpuvm_dev_t vm, const uint32_
 __global__ __launch_bounds__(kBlock) void k_scatter_inc(gpuvm_dev_t vm, const uint32_t *__restrict__ idx, size_t n,
                                                          unsigned long long n_elems) {
     const size_t nthreads = (size_t)gridDim.x * kBlock;
-    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n; k += nthreads) {
-        unsigned long long i = idx[k];
-        if (i >= n_elems) { raise_error(vm, GPUVM_ERANGE); continue; }
-        gpuvm_atomic_add<unsigned long long>(vm, i, 1ull);
+    const size_t n_up = (n + 63) & ~(size_t)63;
+    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n_up; k += nthreads) {
+        unsigned long long i = k < n ? idx[k] : 0;
+        bool want = k < n;
+        if (want && i >= n_elems) { raise_error(vm, GPUVM_ERANGE); want = false; }
+        gpuvm_atomic_add_if<unsigned long long>(vm, i, 1ull, want);
     }
 }
 
@@ -409,16 +412,22 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
 // transfer-bound applications, which has no spatial locality per thread); the
 // 64 lanes of a wave read 256 consecutive bytes of one row.  fp64 accumulation.
 __global__ __launch_bounds__(kBlock) void k_matvec_t(gpuvm_dev_t vm, unsigned long long rows, unsigned long long cols,
-                                                      const float *__restrict__ x, double *__restrict__ y) {
+                                                      unsigned int skew, const float *__restrict__ x,
+                                                      double *__restrict__ y) {
     const size_t nthreads = (size_t)gridDim.x * kBlock;
     const unsigned long long cols_up = (cols + 63) & ~63ull;           // whole waves stay together
     for (unsigned long long j = (size_t)blockIdx.x * kBlock + threadIdx.x; j < cols_up; j += nthreads) {
         double acc = 0.0;
-        if (j < cols) {
-            for (unsigned long long i = 0; i < rows; ++i)
-                acc += (double)gpuvm_load<float>(vm, i * cols + j) * (double)x[i];
-            y[j] = acc;
+        const bool want = j < cols;
+        // Waves that walk down the same rows in lock step would all wait for
+        // the same one or two pages at a time; starting each block of columns
+        // a few rows apart keeps `skew` rows of pages in flight instead.
+        const unsigned long long r0 = (j >> 6) % skew;
+        for (unsigned long long k = 0; k < rows; ++k) {
+            const unsigned long long i = k + r0 < rows ? k + r0 : k + r0 - rows;
+            acc += (double)gpuvm_load_if<float>(vm, want ? i * cols + j : 0, want) * (double)x[i];
         }
+        if (want) y[j] = acc;
     }
 }
 
@@ -442,8 +451,9 @@ __global__ __launch_bounds__(kBlock) void k_filter_sum(gpuvm_dev_t vmk, gpuvm_de
             const unsigned int i = i0 + lane;
             const bool hit = i < n && gpuvm_frame_load_b32(vmk, p, i << 2) > threshold;
             if (__builtin_amdgcn_ballot_w64(hit) == 0) continue;
+            const uint32_t v = gpuvm_load_if<uint32_t>(vmv, hit ? first + i : 0, hit);   // all lanes help to fault
             if (hit) {
-                my_sum += gpuvm_load<uint32_t>(vmv, first + i);
+                my_sum += v;
                 my_count += 1;
             }
         }
@@ -568,12 +578,13 @@ __global__ __launch_bounds__(1024) void k_phase_assign(gpuvm_dev_t vm, const uns
             wb = (pq & GPUVM_PTE_DIRTY) ? 1u : 0u;
             st[GPUVM_S_EVICTIONS] += 1;
             if (wb) { st[GPUVM_S_WB_EVICT] += 1; st[GPUVM_S_BYTES_OUT] += page_len(vm, q); }
-            vm.pte[q] = 0;                                            // INVALID
+            vm.pte[q] = pq & GPUVM_PTE_GEN_MASK;                      // INVALID
             break;
         }
         vm.frame_owner[f] = p;
         vm.pte[p] = (GPUVM_ST_RESIDENT << GPUVM_PTE_STATE_SHIFT) | ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) |
-                    GPUVM_PTE_REF | 1ull;                             // pinned once
+                    GPUVM_PTE_REF | ((vm.pte[p] + (1ull << GPUVM_PTE_GEN_SHIFT)) & GPUVM_PTE_GEN_MASK) |
+                    1ull;                                             // next generation, pinned once
         st[GPUVM_S_FAULTS] += 1;
         st[GPUVM_S_BYTES_IN] += page_len(vm, p);
         jobs[done].page = p; jobs[done].frame = f; jobs[done].victim = victim; jobs[done].writeback = wb;
@@ -1081,7 +1092,10 @@ int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, 
     if (rows * cols * 4 != vm->dev.bytes) return GPUVM_EINVAL;
     const int waves = launch_waves(vm, (cols + 63) / 64);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
-    k_matvec_t<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, d_x, d_y);
+    // rows of A the pool can hold; the start rows are spread over a window well inside it
+    const size_t rows_in_pool = (size_t)vm->dev.n_frames * vm->page_bytes / (cols * 4);
+    const unsigned int skew = (unsigned int)std::max<size_t>(1, std::min<size_t>({(size_t)64, rows_in_pool / 4, rows}));
+    k_matvec_t<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, skew, d_x, d_y);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }

@@ -59,7 +59,10 @@ def check_invariants(b, read_only=True, pristine=None):
     assert len(np.unique(frames)) == len(res), "two pages share a frame"
     assert np.all(owner[frames] == res), "frame table and page table disagree"
     inv = f["state"] == gv.ST_INVALID
-    assert np.all(pte[inv] == 0), "stale bits on an INVALID entry"
+    assert np.all((pte[inv] & ~np.uint64(gv.PTE_GEN_MASK)) == 0), "stale bits on an INVALID entry"
+    # a page's install generation counts its faults (mod 4096)
+    if st["faults"] < 4096:                      # no single page can have wrapped
+        assert int(f["gen"].sum()) == st["faults"]
     assert st["faults"] - st["evictions"] == len(res)
     assert st["writebacks_evict"] <= st["evictions"]
     last_len = b.arr.nbytes - (b.n_pages - 1) * b.page_bytes
