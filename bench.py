@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "filter", "embedding", "scatter"])
-    ap.add_argument("--policy", default="clock", choices=["clock", "fifo"])
+    ap.add_argument("--policy", default="clock", choices=["clock", "fifo", "fifo_wait"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
@@ -598,7 +598,7 @@ def sweep_oversubscription(gv, torch, np, inputs, oracle):
     arr[...] = data
     d_idx = torch.from_numpy(idx.view(np.int32)).cuda()
     d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
-    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO)):
+    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO), ("fifo_wait", gv.POLICY_FIFO_WAIT)):
         base = None
         for lv in levels:
             pool = int(arr.nbytes / (lv + 1)) // page * page
@@ -626,7 +626,7 @@ def sweep_oversubscription(gv, torch, np, inputs, oracle):
     nv = 1 << scale
     want = oracle.bfs(d_rp.cpu().numpy(), carr, 0)
     d_level = torch.zeros(nv, dtype=torch.int32, device="cuda")
-    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO)):
+    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO), ("fifo_wait", gv.POLICY_FIFO_WAIT)):
         base = None
         for lv in levels:
             pool = int(carr.nbytes / (lv + 1)) // page * page
@@ -718,7 +718,7 @@ def main():
     gv.load()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    policy = gv.POLICY_CLOCK if args.policy == "clock" else gv.POLICY_FIFO
+    policy = {"clock": gv.POLICY_CLOCK, "fifo": gv.POLICY_FIFO, "fifo_wait": gv.POLICY_FIFO_WAIT}[args.policy]
 
     if args.sweep:
         import oracle

@@ -8,22 +8,24 @@
  *     float a = gpuvm_load<float>(vm, i);         // any lane, any divergence
  *     gpuvm_store<float>(vm, i, a + 1.0f);
  *     gpuvm_atomic_add<unsigned long long>(vm, i, 1ull);
+ *     float b = gpuvm_load_if<float>(vm, i, in_range);   // whole wave calls, predicate per lane
  *
  * or, for code in which a whole wavefront works on one page at a time,
  *
  *     char *p = gpuvm_acquire(vm, page, write);   // same page in every lane
- *     ... read / write p[0 .. page_bytes) ...
- *     gpuvm_release(vm, page, write);
+ *     ... gpuvm_frame_load_b32/b64/b128(vm, p, byte_offset) ...
+ *     gpuvm_release(vm, page);
  *
  * Execution model.  A CDNA wavefront has no independent thread scheduling, so
  * the fault path is wave-uniform: the accessor loops over the distinct pages
  * its active lanes touch (wavefront dedup, paper: Page access
  * synchronization); for each page the first lane of the group is the leader
  * and performs every atomic, and all active lanes move the page together (the
- * substitute for the paper's NIC work request).  A wave pins ONE page at a
- * time, so pinned frames never exceed the number of waves in flight; the
- * launchers keep that below half the frame pool, which is what makes "pass
- * over a pinned frame" always find a victim.
+ * substitute for the paper's NIC work request).  While it waits or allocates
+ * a wave holds at most ONE frame (a pinned page, or the frame it is filling),
+ * so frames in use never exceed the number of waves in flight; the launchers
+ * keep that below half the frame pool, which is what makes "pass over a
+ * pinned frame" always find a victim.
  *
  * Page-table word (one 64-bit atomic per page, all updates are atomics that
  * leave the pin count of concurrent users intact):
@@ -222,6 +224,7 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
     unsigned int f = 0, victim = GPUVM_NO_PAGE, wb = 0, ok = 1;
     if (w.leader) {
         unsigned long long skips = 0, sweeps = 0;
+        bool redraw = true, waiting = false;
         const unsigned long long budget = 8ull * vm.n_frames + vm.spin_limit;
         for (unsigned long long tries = 0;; ++tries) {
             if (tries > budget || ((tries & 1023) == 1023 && aborted(vm))) {
@@ -229,22 +232,37 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
                 ok = 0;
                 break;
             }
-            const unsigned long long t = a_add(vm.hand, 1ull);
-            f = (unsigned int)(t % vm.n_frames);
-            if (t < vm.n_frames) break;                       /* first turn: frame never used */
+            if (redraw) {
+                const unsigned long long t = a_add(vm.hand, 1ull);
+                f = (unsigned int)(t % vm.n_frames);
+                if (t < vm.n_frames) break;                   /* first turn: frame never used */
+            }
+            redraw = true;
             const unsigned int q = a_load(vm.frame_owner + f);
-            if (q == GPUVM_NO_PAGE) { ++skips; continue; }    /* first install still under way */
-            unsigned long long pq = a_load(vm.pte + q);
-            if (((pq & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT ||
+            unsigned long long pq = q == GPUVM_NO_PAGE ? 0ull : a_load(vm.pte + q);
+            if (q == GPUVM_NO_PAGE ||                          /* first install still under way */
+                ((pq & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT ||
                 (unsigned int)(pq >> GPUVM_PTE_FRAME_SHIFT) != f ||
-                (pq & GPUVM_PTE_PIN_MASK) != 0) { ++skips; continue; }   /* busy or in use */
+                (pq & GPUVM_PTE_PIN_MASK) != 0) {              /* busy or in use */
+                if (vm.policy == GPUVM_POLICY_FIFO_WAIT) {     /* the paper's rule: wait for this frame */
+                    if (!waiting) { waiting = true; stat_add(vm, GPUVM_S_WAITS, 1); }
+                    redraw = false;
+                    __builtin_amdgcn_s_sleep(4);
+                } else {
+                    ++skips;                                   /* this build's default: pass it over */
+                }
+                continue;
+            }
             if (vm.policy == GPUVM_POLICY_CLOCK && (pq & GPUVM_PTE_REF)) {
                 a_and(vm.pte + q, ~GPUVM_PTE_REF);            /* second chance */
                 ++sweeps;
                 continue;
             }
             /* claim the victim; fails if anybody pinned it in the meantime */
-            if (!a_cas(vm.pte + q, &pq, pq | GPUVM_PTE_STATE_MASK)) { ++skips; continue; }
+            if (!a_cas(vm.pte + q, &pq, pq | GPUVM_PTE_STATE_MASK)) {
+                if (vm.policy == GPUVM_POLICY_FIFO_WAIT) redraw = false; else ++skips;
+                continue;
+            }
             victim = q;
             wb = (pq & GPUVM_PTE_DIRTY) ? 1u : 0u;
             break;

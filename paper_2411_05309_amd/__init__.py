@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgpuvm.so")
 
 OK, EINVAL, ENOMEM, EPIN, EDEADLK, EHIP, ERANGE = 0, -1, -2, -3, -4, -5, -6
-POLICY_FIFO, POLICY_CLOCK = 0, 1
+POLICY_FIFO, POLICY_CLOCK, POLICY_FIFO_WAIT = 0, 1, 2
 STAT_NAMES = ("faults", "evictions", "writebacks_evict", "writebacks_flush",
               "bytes_in", "bytes_out", "hits", "wave_page_groups",
               "lanes_coalesced", "loading_waits", "alloc_skips", "alloc_sweeps",

@@ -695,6 +695,7 @@ template <int OP>
 int run_phased(gpuvm_t *vm, const uint32_t *d_idx, size_t n, size_t phase_len, uint32_t *d_out,
                uint64_t *d_sum, void *stream) {
     if (!vm || (!d_idx && n) || phase_len == 0 || phase_len > (1u << 16)) return GPUVM_EINVAL;
+    if (vm->dev.policy == GPUVM_POLICY_FIFO_WAIT) return GPUVM_EINVAL;   // a sequential agent cannot wait
     if (OP == 0 && !d_out && n) return GPUVM_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     int rc = ensure_phase_scratch(vm, phase_len);
@@ -760,7 +761,7 @@ int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_p
     *out = nullptr;
     if (!host_buf || bytes == 0) return GPUVM_EINVAL;
     if (page_bytes < 4096 || page_bytes > (1u << 20) || (page_bytes & (page_bytes - 1))) return GPUVM_EINVAL;
-    if (policy != GPUVM_POLICY_FIFO && policy != GPUVM_POLICY_CLOCK) return GPUVM_EINVAL;
+    if (policy != GPUVM_POLICY_FIFO && policy != GPUVM_POLICY_CLOCK && policy != GPUVM_POLICY_FIFO_WAIT) return GPUVM_EINVAL;
     const size_t n_frames = frame_pool_bytes / page_bytes;
     const size_t n_pages = (bytes + page_bytes - 1) / page_bytes;
     if (n_frames < 2 || n_frames >= (1u << 28) || n_pages >= 0xFFFFFFFFull) return GPUVM_EINVAL;

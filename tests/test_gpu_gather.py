@@ -24,7 +24,7 @@ def run_gather(b, idx, access_stats=False):
     return host(d_out, np.uint32)[:idx.size], int(host(d_sum, np.uint64)[0])
 
 
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO])
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT])
 @pytest.mark.parametrize("n_elems,page,frames,n_idx", [
     (1 << 18, 4096, 64, 1 << 15),          # 256 pages over 64 frames
     ((1 << 18) + 1000, 4096, 16, 10007),   # short last page, ragged index count
@@ -45,6 +45,8 @@ def test_gather_matches_oracle(gpu, policy, n_elems, page, frames, n_idx):
         assert st["faults"] >= distinct
         if distinct <= frames:
             assert st["faults"] == distinct and st["evictions"] == 0
+        if policy == gv.POLICY_FIFO_WAIT:
+            assert st["alloc_skips"] == 0 and st["alloc_sweeps"] == 0   # frames are taken strictly in ring order
         # dedup bookkeeping: every lane is either a group of its own or rides on one
         assert st["wave_page_groups"] + st["lanes_coalesced"] == n_idx
         # every group either found its page resident (at once or after waiting) or faulted

@@ -85,6 +85,15 @@ def test_scatter_phased_equals_sequential_replay(gpu, policy, n_elems, page, fra
         assert np.array_equal(b.arr, direct)
 
 
+def test_phased_mode_refuses_the_waiting_policy(gpu):
+    data = inputs.u32_values(1, 0, 1 << 16)
+    with Backing(data, 4096, 8 * 4096, gv.POLICY_FIFO_WAIT) as b:
+        d_out = torch.zeros(8, dtype=torch.int32, device="cuda")
+        with pytest.raises(gv.GpuvmError) as e:
+            gv.gpuvm_run_gather_phased(b.vm, dev(np.arange(8, dtype=np.uint32)), 8, 4, d_out, None)
+        assert e.value.code == gv.EINVAL
+
+
 def test_phase_with_more_pages_than_frames_is_refused(gpu):
     data = inputs.u32_values(1, 0, 1 << 16)
     with Backing(data, 4096, 8 * 4096) as b:
