@@ -90,6 +90,13 @@ def measure_link(gv, torch, np):
         torch.cuda.synchronize()
         best = max(best, nbytes / (time.perf_counter() - t0) / 1e9)
     res["duplex_each_direction"] = round(best, 2)
+    # unloaded round trip of one 1 KiB wavefront load; with the bandwidth it gives
+    # the bytes that must be in flight to fill the link (Little's law)
+    lat_host = gv.gpuvm_bench_latency(h, nbytes, 4000)
+    lat_hbm = gv.gpuvm_bench_latency(d, nbytes, 4000)
+    res["host_load_latency_us"] = round(lat_host / 1e3, 3)
+    res["hbm_load_latency_us"] = round(lat_hbm / 1e3, 3)
+    res["bytes_in_flight_to_fill_link"] = int(res["wave_read_4k"] * 1e9 * lat_host * 1e-9)
     gv.free_pinned(h2)
     del d, d2, ht
     gv.free_pinned(h)
@@ -804,6 +811,16 @@ def main():
             "hbm_copy_measured_GBps": link["hbm_copy_rw"],
         },
     }
+    tfile = os.path.join(ROOT, "profiles", "traffic_per_launch.txt")
+    if os.path.exists(tfile):                       # counters measured with rocprofv3 --pmc, scaled by faults
+        for line in open(tfile):
+            parts = line.split()
+            if len(parts) > 2 and parts[0] == args.workload and parts[1] == W.kernel:
+                kv = {k: float(v) for k, v in (p.split("=") for p in parts[2:])}
+                scale = st["faults"] / kv["faults"]
+                out["roofline"]["traffic"] = int((kv["host_link_read"] + kv["hbm_read"] + kv["hbm_write"]) * scale)
+                out["roofline"]["traffic_detail"] = {k: int(v * scale) for k, v in kv.items() if k != "faults"}
+                out["roofline"]["traffic_source"] = "profiles/traffic_per_launch.txt (rocprofv3 --pmc), scaled by this run's fault count"
     if hasattr(W, "baselines"):
         out["baselines_same_gpu"] = W.baselines(oracle)
     if not args.no_cpu_baseline:

@@ -281,6 +281,14 @@ GPUVM_API int gpuvm_bench_copy(void *dst, const void *src, size_t bytes,
 GPUVM_API int gpuvm_bench_read(const void *src, size_t bytes, size_t chunk_bytes,
                                int waves, uint64_t *d_sink, void *stream);
 
+/* Unloaded round-trip time of one 1 KiB wavefront load from src (device-visible
+ * pointer, 1 MiB <= bytes <= 2 GiB): one wave, `hops` dependent loads.
+ * *ns_per_hop_out is a host pointer.  Synchronises `stream`.  With the
+ * bandwidth above it gives the bytes that must be in flight to fill the link
+ * (paper: Efficient RDMA I/O Management, the queue-depth argument). */
+GPUVM_API int gpuvm_bench_latency(const void *src, size_t bytes, int hops, double *ns_per_hop_out,
+                                  void *stream);
+
 /* Plain device-resident random gather with no page table (the ceiling for
  * hits): out[k] = data[idx[k]]. */
 GPUVM_API int gpuvm_bench_gather_plain(const uint32_t *d_data, const uint32_t *d_idx,

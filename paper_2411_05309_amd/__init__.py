@@ -90,6 +90,7 @@ _SIGNATURES = {
     "gpuvm_run_scatter_increment_phased": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_bench_copy": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p], C.c_int),
     "gpuvm_bench_read": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_bench_latency": ([C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.c_void_p], C.c_int),
     "gpuvm_bench_gather_plain": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
 }
 
@@ -273,6 +274,12 @@ def gpuvm_bench_copy(dst, src, nbytes, chunk_bytes, waves=0, stream=None):
 
 def gpuvm_bench_read(src, nbytes, chunk_bytes, d_sink, waves=0, stream=None):
     _call("gpuvm_bench_read", _ptr(src), nbytes, chunk_bytes, waves, _ptr(d_sink), _stream(stream))
+
+
+def gpuvm_bench_latency(src, nbytes, hops=2000, stream=None):
+    ns = C.c_double(0.0)
+    _call("gpuvm_bench_latency", _ptr(src), nbytes, hops, C.byref(ns), _stream(stream))
+    return ns.value
 
 
 def gpuvm_bench_gather_plain(d_data, d_idx, n, d_out, stream=None):

@@ -506,6 +506,24 @@ __global__ __launch_bounds__(kBlock) void k_bench_read(const char *src, size_t b
     if (v == 0x9E3779B97F4A7C15ull) sink[0] = v;   // practically never: keeps the loads alive
 }
 
+// One wave, a chain of dependent 16-byte-per-lane loads (1 KiB per hop, the
+// mover's instruction): the unloaded round-trip time of the memory behind src.
+__global__ __launch_bounds__(64) void k_bench_latency(const char *src, unsigned int bytes, unsigned int hops,
+                                                       unsigned int zero, unsigned long long *out) {
+    const unsigned int lane = threadIdx.x & 63;
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(src, bytes);
+    unsigned int off = lane * 16u, acc = 0;
+    const unsigned int span = bytes - 1024u;
+    const unsigned long long t0 = wall_clock64();
+    for (unsigned int h = 0; h < hops; ++h) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, GPUVM_AUX_SYSTEM);
+        acc ^= v.x;
+        off = (off + 69632u + (v.x & zero)) % span / 1024u * 1024u + lane * 16u;   // next hop needs this one's data
+    }
+    const unsigned long long t1 = wall_clock64();
+    if (lane == 0) { out[0] = t1 - t0; out[1] = acc; }
+}
+
 __global__ __launch_bounds__(kBlock) void k_bench_gather_plain(const uint32_t *__restrict__ data,
                                                                 const uint32_t *__restrict__ idx, size_t n,
                                                                 uint32_t *__restrict__ out) {
@@ -1155,6 +1173,23 @@ int gpuvm_bench_read(const void *src, size_t bytes, size_t chunk_bytes, int wave
                                                                                           chunk_bytes,
                                                                                           (unsigned long long *)d_sink);
     HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_bench_latency(const void *src, size_t bytes, int hops, double *ns_per_hop_out, void *stream) {
+    if (!src || !ns_per_hop_out || bytes < (1u << 20) || bytes > (1u << 31) || hops < 1) return GPUVM_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned long long *d_out = nullptr, h_out[2] = {0, 0};
+    HIP_TRY(hipMalloc(&d_out, 2 * sizeof(unsigned long long)));
+    int dev = 0, khz = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    k_bench_latency<<<1, 64, 0, s>>>((const char *)src, (unsigned int)bytes, (unsigned int)hops, 0u, d_out);
+    hipError_t e = hipMemcpyAsync(h_out, d_out, sizeof(h_out), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(d_out);
+    if (e != hipSuccess || khz <= 0) return GPUVM_EHIP;
+    *ns_per_hop_out = (double)h_out[0] * 1e6 / (double)khz / (double)hops;
     return GPUVM_OK;
 }
 
