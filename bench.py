@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "filter", "embedding", "scatter"])
+    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "filter", "vector_add", "embedding", "scatter"])
     ap.add_argument("--policy", default="clock", choices=["clock", "fifo", "fifo_wait"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -252,6 +252,56 @@ class StreamWorkload:
 
     def config(self):
         return {"floats": self.n_floats, "passes": self.passes, "block_elems": self.block}
+
+
+class VectorAddWorkload:
+    """The paper's vector addition: C = A + B, three fp32 vectors of 2^31 elements
+    (8 GiB each) paged from host, 64 KiB pages, 2 GiB pool each; C is flushed."""
+    n, page, pool = 1 << 31, 65536, 2 << 30
+    dtype = "f32"
+    kernel = "k_vector_add"
+    name = "vector_add_3x8GiB_f32_64KiB_pages_2GiB_pools_then_flush"
+
+    def __init__(self, gv, torch, np, inputs, policy):
+        self.gv, self.torch, self.np = gv, torch, np
+        self.arr = gv.pinned_array((self.n,), np.float32)                   # A
+        self.barr = gv.pinned_array((self.n,), np.float32)
+        self.carr = gv.pinned_array((self.n,), np.float32)
+        ha, hb = torch.from_numpy(self.arr), torch.from_numpy(self.barr)
+        for lo in range(0, self.n, 1 << 26):
+            ha[lo:lo + (1 << 26)].copy_(inputs.t_f32_uniform(1, lo, 1 << 26, "cuda"))
+            hb[lo:lo + (1 << 26)].copy_(inputs.t_f32_uniform(2, lo, 1 << 26, "cuda"))
+        torch.cuda.synchronize()
+        self.vm = gv.gpuvm_create(self.arr.ctypes.data, self.arr.nbytes, self.page, self.pool, policy)
+        self.vmb = gv.gpuvm_create(self.barr.ctypes.data, self.barr.nbytes, self.page, self.pool, policy)
+        self.vmc = gv.gpuvm_create(self.carr.ctypes.data, self.carr.nbytes, self.page, self.pool, policy)
+        self.useful_bytes = 12 * self.n
+
+    def launch(self):
+        gv = self.gv
+        gv.gpuvm_reset(self.vmb)
+        gv.gpuvm_reset(self.vmc)
+        gv.gpuvm_run_vector_add(self.vm, self.vmb, self.vmc, self.n)
+        gv.gpuvm_flush(self.vmc)
+        sb, sc = gv.gpuvm_stats(self.vmb), gv.gpuvm_stats(self.vmc)
+        self.stats_w = {k: sb[k] + sc[k] for k in sb}
+
+    def verify(self, oracle):
+        np = self.np
+        ok = True
+        for lo in np.linspace(0, self.n - (1 << 20), 24).astype(np.int64):
+            sl = slice(int(lo), int(lo) + (1 << 20))
+            ok &= bool(np.array_equal(self.carr[sl], oracle.vector_add(self.arr[sl], self.barr[sl])))
+        return ok
+
+    def cpu_baseline(self, oracle):
+        k = 1 << 27
+        t0 = time.perf_counter()
+        oracle.vector_add(self.arr[:k], self.barr[:k])
+        return (time.perf_counter() - t0) * (self.n / k), "2^27 of the 2^31 elements, scaled"
+
+    def config(self):
+        return {"elements": self.n}
 
 
 class BfsWorkload:
@@ -573,9 +623,9 @@ class ScatterWorkload:
 
 
 WORKLOADS = {"gather": GatherWorkload, "stream": StreamWorkload, "bfs": BfsWorkload, "cc": CcWorkload, "sssp": SsspWorkload,
-             "matvec_t": MatvecTWorkload, "filter": FilterWorkload,
+             "matvec_t": MatvecTWorkload, "filter": FilterWorkload, "vector_add": VectorAddWorkload,
              "embedding": EmbeddingWorkload, "scatter": ScatterWorkload}
-DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "matvec_t": (3, 1), "filter": (5, 1), "embedding": (2, 1), "scatter": (1, 0)}
+DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "matvec_t": (3, 1), "filter": (5, 1), "vector_add": (3, 1), "embedding": (2, 1), "scatter": (1, 0)}
 
 
 def timed_ms(torch, fn, reps=3):

@@ -179,6 +179,13 @@ GPUVM_API const char *gpuvm_strerror(int code);
 GPUVM_API int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n,
                                uint32_t *d_out, uint64_t *d_sum, void *stream);
 
+/* The paper's vector-addition listing: C[i] = A[i] + B[i] for i < n over three
+ * paged fp32 vectors (three handles, each with its own frame pool; A and B may
+ * be the same handle, C must be distinct).  C is written with gpuvm_store, its
+ * pages become DIRTY and reach the host at eviction or gpuvm_flush(vm_c). */
+GPUVM_API int gpuvm_run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n,
+                                   void *stream);
+
 /* One pass of a streaming read-reduce over an fp32 data set: for each block of
  * block_elems consecutive floats (a multiple of the page's float count),
  * d_sums[b] = sum in fp64.  One wavefront per page, consecutive pages to

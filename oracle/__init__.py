@@ -48,6 +48,7 @@ def lib():
         L = C.CDLL(_LIB)
         vp, u64, i64 = C.c_void_p, C.c_uint64, C.c_int64
         L.oracle_gather.argtypes = [vp, vp, u64, vp, vp]
+        L.oracle_vector_add.argtypes = [vp, vp, vp, u64]
         L.oracle_stream_reduce.argtypes = [vp, u64, u64, C.c_int, vp]
         L.oracle_stream_abs.argtypes = [vp, u64, u64, vp]
         L.oracle_bfs.argtypes = [vp, vp, i64, i64, vp]
@@ -98,6 +99,16 @@ def gather(host, idx):
     s = np.zeros(1, np.uint64)
     lib().oracle_gather(_p(host), _p(idx), idx.size, _p(out), _p(s))
     return out, int(s[0])
+
+
+def vector_add(a, b):
+    """c[i] = a[i] + b[i] in fp32."""
+    a = _arr(a, np.float32)
+    b = _arr(b, np.float32)
+    assert a.shape == b.shape
+    c = np.empty_like(a)
+    lib().oracle_vector_add(_p(a), _p(b), _p(c), a.size)
+    return c
 
 
 def stream_reduce(x, block_elems, passes):

@@ -57,6 +57,15 @@ void oracle_gather(const uint32_t *host, const uint32_t *idx, uint64_t n,
     *sum = s;
 }
 
+/* Vector addition (the paper's listing): c[i] = a[i] + b[i], one fp32 rounding. */
+void oracle_vector_add(const float *a, const float *b, float *c, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        volatile float s = a[i] + b[i];
+        c[i] = s;
+    }
+}
+
 /* Streaming read-reduce: for every pass and every block of block_elems
  * consecutive floats, the double-precision sum taken in index order.
  * s is laid out [pass][block]; the last block may be short. */

@@ -77,6 +77,7 @@ _SIGNATURES = {
     "gpuvm_dump_tables": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_strerror": ([C.c_int], C.c_char_p),
     "gpuvm_run_gather": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_run_vector_add": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_stream_reduce": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_bfs": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_bfs_balanced": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
@@ -213,6 +214,10 @@ def gpuvm_dump_tables(vm):
 
 def gpuvm_run_gather(vm, d_idx, n, d_out, d_sum=None, stream=None):
     _call("gpuvm_run_gather", vm, _ptr(d_idx), n, _ptr(d_out), _ptr(d_sum), _stream(stream))
+
+
+def gpuvm_run_vector_add(vm_a, vm_b, vm_c, n, stream=None):
+    _call("gpuvm_run_vector_add", vm_a, vm_b, vm_c, n, _stream(stream))
 
 
 def gpuvm_run_stream_reduce(vm, block_elems, d_sums, stream=None):

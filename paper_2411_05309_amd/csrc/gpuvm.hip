@@ -136,6 +136,30 @@ __global__ __launch_bounds__(kBlock) void k_scatter_inc(gpuvm_dev_t vm, const ui
     }
 }
 
+// The paper's own example (vector-addition listing): C[i] = A[i] + B[i] with all
+// three vectors paged; C is written through gpuvm_store, so its pages become
+// DIRTY and are written back at eviction or flush.
+// Work distribution: a wave takes one page-sized stripe of the index range at a
+// time (consecutive stripes to consecutive waves), so that the waves in flight
+// fault on different pages; with a plain grid-stride loop all of them would
+// stand on the same handful of pages and wait for one fetch at a time.
+__global__ __launch_bounds__(kBlock) void k_vector_add(gpuvm_dev_t a, gpuvm_dev_t b, gpuvm_dev_t c, size_t n) {
+    const unsigned int lane = threadIdx.x & 63;
+    const size_t wave = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
+    const size_t stripe = (size_t)1 << (c.page_shift - 2);               // floats per page of C
+    for (size_t lo = wave * stripe; lo < n; lo += nwaves * stripe) {
+        const size_t hi = lo + stripe < n ? lo + stripe : n;
+        for (size_t i0 = lo; i0 < hi; i0 += 64) {
+            const size_t i = i0 + lane;
+            const bool want = i < hi;
+            const float x = gpuvm_load_if<float>(a, want ? i : 0, want);
+            const float y = gpuvm_load_if<float>(b, want ? i : 0, want);
+            gpuvm_store_if<float>(c, want ? i : 0, x + y, want);
+        }
+    }
+}
+
 // Streaming read-reduce: wave w takes pages w, w + nwaves, ...; the page's
 // floats are summed in fp64 and added to the sum of the block it belongs to.
 __global__ __launch_bounds__(kBlock) void k_stream_reduce(gpuvm_dev_t vm, unsigned int pages_per_block,
@@ -949,6 +973,18 @@ int gpuvm_run_scatter_increment(gpuvm_t *vm, const uint32_t *d_idx, size_t n, vo
     const int waves = launch_waves(vm, (n + 63) / 64);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
     k_scatter_inc<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, vm->dev.bytes / 8);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n, void *stream) {
+    if (!vm_a || !vm_b || !vm_c || vm_a == vm_c || vm_b == vm_c) return GPUVM_EINVAL;
+    if (n * 4 > vm_a->dev.bytes || n * 4 > vm_b->dev.bytes || n * 4 > vm_c->dev.bytes) return GPUVM_ERANGE;
+    if (n == 0) return GPUVM_OK;
+    const size_t work = (n * 4 + vm_c->page_bytes - 1) / vm_c->page_bytes;       // page-sized stripes
+    const int waves = std::min({launch_waves(vm_a, work), launch_waves(vm_b, work), launch_waves(vm_c, work)});
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    k_vector_add<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, vm_c->dev, n);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }

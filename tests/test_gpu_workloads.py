@@ -266,3 +266,30 @@ def test_filter_sum(gpu, n, page, frames, sel):
         assert stv["faults"] >= touched                              # only pages with a matching row are fetched
         if sel < 0.001:
             assert stv["faults"] < 2 * bv.n_pages * 0.8             # well below two full scans
+
+
+# ---------------------------------------------------------------- the paper's vector addition (stores)
+
+@pytest.mark.parametrize("n,page,frames", [(1 << 20, 65536, 16), ((1 << 18) + 777, 4096, 16), (5000, 4096, 8)])
+def test_vector_add_through_three_paged_vectors(gpu, n, page, frames):
+    a = inputs.f32_uniform(1, 0, n)
+    b = inputs.f32_uniform(2, 0, n)
+    want = oracle.vector_add(a, b)
+    with Backing(a, page, frames * page) as ba, Backing(b, page, frames * page) as bb, \
+            Backing(np.full(n, -9.0, np.float32), page, frames * page) as bc:
+        gv.gpuvm_run_vector_add(ba.vm, bb.vm, bc.vm, n)
+        for x in (ba, bb, bc):
+            gv.gpuvm_check(x.vm)
+        check_invariants(ba, read_only=True, pristine=a)
+        check_invariants(bb, read_only=True, pristine=b)
+        stc, fc, *_ = check_invariants(bc, read_only=False)
+        if bc.n_pages > frames:
+            assert stc["writebacks_evict"] > 0
+        gv.gpuvm_flush(bc.vm)
+        assert np.array_equal(bc.arr, want)                              # bit-exact fp32
+        # in place: A += A (A and B the same handle), result in C
+        gv.gpuvm_run_vector_add(ba.vm, ba.vm, bc.vm, n)
+        gv.gpuvm_flush(bc.vm)
+        assert np.array_equal(bc.arr, oracle.vector_add(a, a))
+        with pytest.raises(gv.GpuvmError):
+            gv.gpuvm_run_vector_add(ba.vm, bb.vm, ba.vm, n)

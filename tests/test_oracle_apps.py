@@ -269,3 +269,13 @@ def test_filter_sum_against_numpy():
     assert oracle.filter_sum(key, val, 0xFFFFFFFF) == (0, 0)
     assert oracle.filter_sum(key[:0], val[:0], 5) == (0, 0)
     assert oracle.filter_sum(np.array([6, 5, 7], np.uint32), np.array([1, 2, 4], np.uint32), 5) == (2, 5)
+
+
+def test_vector_add_is_ieee_fp32_addition():
+    a = inputs.f32_uniform(1, 0, 10001)
+    b = inputs.f32_uniform(2, 0, 10001) * np.float32(1e-3)
+    c = oracle.vector_add(a, b)
+    assert c.dtype == np.float32 and np.array_equal(c, a + b)            # numpy's fp32 add
+    exact = a.astype(np.float64) + b.astype(np.float64)
+    assert np.all(np.abs(c - exact) <= np.abs(exact) * 2.0 ** -24 + 1e-45)  # correctly rounded
+    assert oracle.vector_add(np.array([1.0, -2.5], np.float32), np.array([2.0, 2.5], np.float32)).tolist() == [3.0, 0.0]
