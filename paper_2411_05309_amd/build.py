@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = [os.path.join(HERE, "csrc", "gpuvm.hip")]
+SRC = [os.path.join(HERE, "csrc", f) for f in ("core.hip", "workloads.hip", "graph.hip", "phased.hip", "roofline.hip")]
 LIB = os.path.join(HERE, "libgpuvm.so")
 
 FLAGS = [
@@ -14,7 +14,7 @@ FLAGS = [
     # packed fp32 forms are not to be generated on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
-    "-I", os.path.join(ROOT, "include"),
+    "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
 ]
 
 

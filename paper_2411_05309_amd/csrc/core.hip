@@ -1,0 +1,238 @@
+// libgpuvm - life cycle of a paged view, flush / reset / counters, launch-shape helpers.
+// The fault path itself (page-table lookup, wavefront dedup, frame allocation,
+// eviction, write-back, migration) is in include/gpuvm_device.h and is inlined
+// into every kernel, the way the paper inlines its runtime into the application
+// kernels (System Overview; Register usage).
+#include "gpuvm_internal.h"
+
+using namespace gpuvm_detail;
+
+#include <new>
+#include <vector>
+
+// One wavefront per frame: write a DIRTY page back and clear the bit.  Runs
+// alone (no other kernel on the handle), so plain table reads are enough.
+__global__ __launch_bounds__(kBlock) void k_flush(gpuvm_dev_t vm) {
+    const wave_t w = wave_now();
+    const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const unsigned int nwaves = (gridDim.x * kBlock) >> 6;
+    for (unsigned int f = wave; f < vm.n_frames; f += nwaves) {
+        const unsigned int q = vm.frame_owner[f];
+        if (q == GPUVM_NO_PAGE) continue;
+        const unsigned long long pq = vm.pte[q];
+        if (((pq & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT ||
+            (unsigned int)(pq >> GPUVM_PTE_FRAME_SHIFT) != f || !(pq & GPUVM_PTE_DIRTY))
+            continue;
+        const unsigned int len = page_len(vm, q);
+        copy_frame_to_host(vm.host + ((size_t)q << vm.page_shift), vm.frames + ((size_t)f << vm.page_shift), len, w);
+        if (w.leader) {
+            a_and(vm.pte + q, ~GPUVM_PTE_DIRTY);
+            stat_add(vm, GPUVM_S_WB_FLUSH, 1);
+            stat_add(vm, GPUVM_S_BYTES_OUT, len);
+        }
+    }
+    wait_vm();
+}
+
+int check_kernel_error(gpuvm_t *vm) {
+    unsigned long long word = 0;
+    HIP_TRY(hipMemcpy(&word, vm->dev.hand + 1, sizeof(word), hipMemcpyDeviceToHost));
+    return word ? -(int)word : GPUVM_OK;
+}
+
+int grid_for_waves(int waves) { return std::max(1, waves / kWavesPerBlock); }
+
+int launch_waves(const gpuvm_t *vm, size_t work_waves) {
+    // waves in flight: enough to fill the device, never more than half the
+    // frames, whole workgroups; 0 if not even one workgroup may run
+    long long cap = std::min<long long>((long long)vm->cus * vm->waves_per_cu, vm->dev.n_frames / 2);
+    cap = (cap / kWavesPerBlock) * kWavesPerBlock;
+    const long long need = (long long)((std::max<size_t>(work_waves, 1) + kWavesPerBlock - 1) / kWavesPerBlock) * kWavesPerBlock;
+    return (int)std::min(cap, need);
+}
+
+extern "C" {
+
+const char *gpuvm_strerror(int code) {
+    switch (code) {
+        case GPUVM_OK: return "ok";
+        case GPUVM_EINVAL: return "invalid argument";
+        case GPUVM_ENOMEM: return "out of memory";
+        case GPUVM_EPIN: return "host buffer is not pinned GPU-mapped memory";
+        case GPUVM_EDEADLK: return "frame pool too small for the waves in flight, or a bounded in-kernel wait ran out";
+        case GPUVM_EHIP: return "HIP runtime error";
+        case GPUVM_ERANGE: return "index outside the data set";
+        default: return "unknown gpuvm error";
+    }
+}
+
+int gpuvm_host_alloc(size_t bytes, void **out) {
+    if (!out || bytes == 0) return GPUVM_EINVAL;
+    *out = nullptr;
+    hipError_t e = hipHostMalloc(out, bytes, hipHostMallocDefault);
+    if (e != hipSuccess) { (void)hipGetLastError(); *out = nullptr; return GPUVM_ENOMEM; }
+    return GPUVM_OK;
+}
+
+int gpuvm_host_free(void *p) {
+    if (!p) return GPUVM_OK;
+    HIP_TRY(hipHostFree(p));
+    return GPUVM_OK;
+}
+
+int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_pool_bytes, int policy,
+                 gpuvm_t **out) {
+    if (!out) return GPUVM_EINVAL;
+    *out = nullptr;
+    if (!host_buf || bytes == 0) return GPUVM_EINVAL;
+    if (page_bytes < 4096 || page_bytes > (1u << 20) || (page_bytes & (page_bytes - 1))) return GPUVM_EINVAL;
+    if (policy != GPUVM_POLICY_FIFO && policy != GPUVM_POLICY_CLOCK && policy != GPUVM_POLICY_FIFO_WAIT) return GPUVM_EINVAL;
+    const size_t n_frames = frame_pool_bytes / page_bytes;
+    const size_t n_pages = (bytes + page_bytes - 1) / page_bytes;
+    if (n_frames < 2 || n_frames >= (1u << 28) || n_pages >= 0xFFFFFFFFull) return GPUVM_EINVAL;
+
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, host_buf) != hipSuccess) { (void)hipGetLastError(); return GPUVM_EPIN; }
+    if (attr.type != hipMemoryTypeHost || !attr.devicePointer) return GPUVM_EPIN;
+    // the whole range must lie inside the pinned allocation
+    hipPointerAttribute_t last;
+    if (hipPointerGetAttributes(&last, (char *)host_buf + bytes - 1) != hipSuccess ||
+        last.type != hipMemoryTypeHost) { (void)hipGetLastError(); return GPUVM_EPIN; }
+
+    gpuvm_t *vm = new (std::nothrow) gpuvm();
+    if (!vm) return GPUVM_ENOMEM;
+    memset(&vm->dev, 0, sizeof(vm->dev));
+    HIP_TRY(hipGetDevice(&vm->device));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, vm->device));
+    vm->cus = prop.multiProcessorCount;
+    vm->waves_per_cu = 8;
+    if (const char *e = getenv("GPUVM_WAVES_PER_CU")) vm->waves_per_cu = std::max(1, std::min(32, atoi(e)));
+    vm->page_bytes = page_bytes;
+    gpuvm_dev_t &d = vm->dev;
+    d.host = (char *)attr.devicePointer;
+    d.bytes = bytes;
+    d.n_pages = (uint32_t)n_pages;
+    d.n_frames = (uint32_t)n_frames;
+    d.page_shift = (uint32_t)__builtin_ctzll(page_bytes);
+    d.policy = (uint32_t)policy;
+    d.spin_limit = kDefaultSpinLimit;
+    d.flags = 0;
+    int rc = GPUVM_OK;
+    auto alloc = [&](void **p, size_t sz) {
+        if (rc) return;
+        if (hipMalloc(p, sz) != hipSuccess) { (void)hipGetLastError(); rc = GPUVM_ENOMEM; }
+    };
+    alloc((void **)&d.frames, n_frames * page_bytes);
+    alloc((void **)&d.pte, n_pages * sizeof(unsigned long long));
+    alloc((void **)&d.frame_owner, n_frames * sizeof(unsigned int));
+    alloc((void **)&d.hand, 2 * sizeof(unsigned long long));
+    alloc((void **)&d.stats, (size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT * sizeof(unsigned long long));
+    alloc((void **)&vm->bfs_changed, sizeof(int));
+    if (rc) { gpuvm_destroy(vm); return rc; }
+    k_fill64<<<256, 256>>>(d.pte, n_pages, 0ull);
+    k_fill32<<<256, 256>>>(d.frame_owner, n_frames, GPUVM_NO_PAGE);
+    k_fill64<<<1, 64>>>(d.hand, 2, 0ull);
+    k_fill64<<<4, 256>>>(d.stats, (size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT, 0ull);
+    if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); gpuvm_destroy(vm); return GPUVM_EHIP; }
+    *out = vm;
+    return GPUVM_OK;
+}
+
+int gpuvm_destroy(gpuvm_t *vm) {
+    if (!vm) return GPUVM_OK;
+    (void)hipDeviceSynchronize();
+    gpuvm_dev_t &d = vm->dev;
+    (void)hipFree(d.frames); (void)hipFree(d.pte); (void)hipFree(d.frame_owner); (void)hipFree(d.hand); (void)hipFree(d.stats);
+    (void)hipFree(vm->stamp); (void)hipFree(vm->first); (void)hipFree(vm->miss); (void)hipFree(vm->miss_sorted); (void)hipFree(vm->jobs);
+    (void)hipFree(vm->phase_ctr); (void)hipFree(vm->bfs_changed); (void)hipFree(vm->page_owner);
+    delete vm;
+    return GPUVM_OK;
+}
+
+int gpuvm_device_handle(const gpuvm_t *vm, gpuvm_dev_t *out) {
+    if (!vm || !out) return GPUVM_EINVAL;
+    *out = vm->dev;
+    return GPUVM_OK;
+}
+
+int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats) {
+    if (!vm) return GPUVM_EINVAL;
+    vm->dev.spin_limit = spin_limit ? spin_limit : kDefaultSpinLimit;
+    vm->dev.flags = access_stats ? (vm->dev.flags | GPUVM_F_ACCESS_STATS) : (vm->dev.flags & ~GPUVM_F_ACCESS_STATS);
+    return GPUVM_OK;
+}
+
+int gpuvm_set_waves_per_cu(gpuvm_t *vm, int waves_per_cu) {
+    if (!vm || waves_per_cu < 1 || waves_per_cu > 32) return GPUVM_EINVAL;
+    vm->waves_per_cu = waves_per_cu;
+    return GPUVM_OK;
+}
+
+int gpuvm_max_waves(const gpuvm_t *vm) {
+    if (!vm) return GPUVM_EINVAL;
+    return launch_waves(vm, (size_t)1 << 40);
+}
+
+int gpuvm_flush(gpuvm_t *vm, void *stream) {
+    if (!vm) return GPUVM_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int waves = std::max(kWavesPerBlock, std::min<int>(vm->cus * 8, (int)std::min<size_t>(vm->dev.n_frames, 1 << 20)));
+    k_flush<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(s));
+    return check_kernel_error(vm);
+}
+
+int gpuvm_reset(gpuvm_t *vm, void *stream) {
+    if (!vm) return GPUVM_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int waves = std::max(kWavesPerBlock, std::min<int>(vm->cus * 8, (int)std::min<size_t>(vm->dev.n_frames, 1 << 20)));
+    k_flush<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev);
+    gpuvm_dev_t &d = vm->dev;
+    k_fill64<<<256, 256, 0, s>>>(d.pte, d.n_pages, 0ull);
+    k_fill32<<<256, 256, 0, s>>>(d.frame_owner, d.n_frames, GPUVM_NO_PAGE);
+    k_fill64<<<1, 64, 0, s>>>(d.hand, 2, 0ull);
+    k_fill64<<<4, 256, 0, s>>>(d.stats, (size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT, 0ull);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(s));
+    return GPUVM_OK;
+}
+
+int gpuvm_stats(gpuvm_t *vm, gpuvm_stats_t *out) {
+    if (!vm || !out) return GPUVM_EINVAL;
+    HIP_TRY(hipDeviceSynchronize());
+    std::vector<unsigned long long> raw((size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT);
+    HIP_TRY(hipMemcpy(raw.data(), vm->dev.stats, raw.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+    uint64_t tot[GPUVM_S_COUNT] = {0};
+    for (int s = 0; s < GPUVM_STAT_SLOTS; ++s)
+        for (int c = 0; c < GPUVM_S_COUNT; ++c) tot[c] += raw[(size_t)s * GPUVM_S_COUNT + c];
+    static_assert(sizeof(gpuvm_stats_t) == GPUVM_S_COUNT * sizeof(uint64_t), "stats layout");
+    memcpy(out, tot, sizeof(tot));
+    return check_kernel_error(vm);
+}
+
+int gpuvm_stats_clear(gpuvm_t *vm) {
+    if (!vm) return GPUVM_EINVAL;
+    HIP_TRY(hipDeviceSynchronize());
+    k_fill64<<<4, 256>>>(vm->dev.stats, (size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT, 0ull);
+    HIP_TRY(hipDeviceSynchronize());
+    return GPUVM_OK;
+}
+
+int gpuvm_dump_tables(gpuvm_t *vm, uint64_t *pte_out, uint32_t *owner_out, uint64_t *hand_out) {
+    if (!vm) return GPUVM_EINVAL;
+    HIP_TRY(hipDeviceSynchronize());
+    if (pte_out) HIP_TRY(hipMemcpy(pte_out, vm->dev.pte, (size_t)vm->dev.n_pages * 8, hipMemcpyDeviceToHost));
+    if (owner_out) HIP_TRY(hipMemcpy(owner_out, vm->dev.frame_owner, (size_t)vm->dev.n_frames * 4, hipMemcpyDeviceToHost));
+    if (hand_out) HIP_TRY(hipMemcpy(hand_out, vm->dev.hand, 8, hipMemcpyDeviceToHost));
+    return check_kernel_error(vm);
+}
+
+int gpuvm_check(gpuvm_t *vm, void *stream) {
+    if (!vm) return GPUVM_EINVAL;
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    return check_kernel_error(vm);
+}
+
+}  // extern "C"

@@ -1,0 +1,325 @@
+// libgpuvm - graph workloads over a paged CSR col_idx array: BFS (vertex chunks and edge-balanced), connected components, SSSP with paged weights.
+// The fault path itself (page-table lookup, wavefront dedup, frame allocation,
+// eviction, write-back, migration) is in include/gpuvm_device.h and is inlined
+// into every kernel, the way the paper inlines its runtime into the application
+// kernels (System Overview; Register usage).
+#include "gpuvm_internal.h"
+
+using namespace gpuvm_detail;
+
+// One BFS level, topology driven: a wave scans 64 consecutive vertices; the
+// edges of each vertex on the current level are read from the paged col_idx
+// array by the whole wave, page by page, keeping one page pinned at a time.
+__global__ __launch_bounds__(kBlock) void k_bfs_level(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
+                                                       int64_t nv, int32_t *level, int32_t cur, int *changed) {
+    const unsigned int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
+    const unsigned int elems_shift = vm.page_shift - 2;                // int32 per page
+    int found = 0;
+    for (int64_t base = wave * 64; base < nv; base += nwaves * 64) {
+        const int64_t v = base + lane;
+        int64_t beg = 0, end = 0;
+        if (v < nv && level[v] == cur) { beg = row_ptr[v]; end = row_ptr[v + 1]; }
+        unsigned long long todo = __builtin_amdgcn_ballot_w64(end > beg);
+        unsigned int held = GPUVM_NO_PAGE;
+        const char *ptr = nullptr;
+        while (todo) {
+            const unsigned int l = (unsigned int)__ffsll((long long)todo) - 1u;
+            todo &= todo - 1;
+            const int64_t b = ((int64_t)__builtin_amdgcn_readlane((int)(beg >> 32), l) << 32) |
+                              (unsigned int)__builtin_amdgcn_readlane((int)beg, l);
+            const int64_t e = ((int64_t)__builtin_amdgcn_readlane((int)(end >> 32), l) << 32) |
+                              (unsigned int)__builtin_amdgcn_readlane((int)end, l);
+            for (int64_t pos = b; pos < e;) {
+                const unsigned int page = (unsigned int)(pos >> elems_shift);
+                const int64_t page_first = (int64_t)page << elems_shift;
+                const int64_t page_stop = page_first + ((int64_t)1 << elems_shift);
+                const int64_t stop = e < page_stop ? e : page_stop;
+                if (page != held) {
+                    if (held != GPUVM_NO_PAGE) gpuvm_release(vm, held);
+                    ptr = gpuvm_acquire(vm, page, false);
+                    held = page;
+                }
+                for (int64_t i = pos + lane; i < stop; i += 64) {
+                    const int32_t u = (int32_t)gpuvm_frame_load_b32(vm, ptr, (unsigned int)(i - page_first) << 2);
+                    if (level[u] < 0) { level[u] = cur + 1; found = 1; }
+                }
+                pos = stop;
+            }
+        }
+        if (held != GPUVM_NO_PAGE) gpuvm_release(vm, held);
+    }
+    if (__builtin_amdgcn_ballot_w64(found != 0) && lane == 0) *changed = 1;
+}
+
+// ---- edge-balanced BFS (the paper's Balanced CSR idea, Graph Workloads: equal
+// chunks of edges per worker so that faults do not serialise behind the huge
+// neighbour lists).  The chunk is one page of col_idx: a wave owns page p for
+// the level, so every page is faulted by at most one wave per level and no
+// vertex, however large, is walked by a single wave.
+// page_owner[p] = vertex that owns the first edge of page p (owner[n_pages] = nv-1).
+__global__ void k_bfs_page_owner(const int64_t *__restrict__ row_ptr, int64_t nv, unsigned int n_pages,
+                                 unsigned int elems_shift, unsigned int *page_owner) {
+    const unsigned int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > n_pages) return;
+    if (p == n_pages) { page_owner[p] = (unsigned int)(nv - 1); return; }
+    const int64_t e = (int64_t)p << elems_shift;
+    int64_t lo = 0, hi = nv;                      // last v with row_ptr[v] <= e
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (row_ptr[mid] <= e) lo = mid; else hi = mid;
+    }
+    page_owner[p] = (unsigned int)lo;
+}
+
+// Page-owned edge walk shared by the edge-balanced graph kernels: wave w owns
+// pages w, w + nwaves, ... of the paged col_idx array for this round; inside a
+// page it visits the edge segments of the vertices for which active(v) holds.
+// Short segments are walked one lane per vertex, long ones by the whole wave.
+// visit(v, u, byte_off, ptr2): edge v -> u stored at byte_off of the page; ptr2
+// is the frame of the same page of a second paged array (edge weights) or null.
+template <class Active, class Visit>
+__device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gpuvm_dev_t *vm2,
+                                                 const int64_t *__restrict__ row_ptr,
+                                                 const unsigned int *__restrict__ page_owner,
+                                                 Active active, Visit visit) {
+    const unsigned int lane = threadIdx.x & 63;
+    const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const unsigned int nwaves = (gridDim.x * kBlock) >> 6;
+    const unsigned int elems_shift = vm.page_shift - 2;
+    const int64_t n_edges = (int64_t)(vm.bytes >> 2);
+    constexpr int kSmall = 32;                    // lists up to this length: one lane each
+    for (unsigned int page = wave; page < vm.n_pages; page += nwaves) {
+        const int64_t e_lo = (int64_t)page << elems_shift;
+        const int64_t e_hi = min((long long)n_edges, (long long)(e_lo + ((int64_t)1 << elems_shift)));
+        const int64_t v_first = page_owner[page], v_last = page_owner[page + 1];
+        const char *ptr = nullptr, *ptr2 = nullptr;
+        for (int64_t vb = v_first; vb <= v_last; vb += 64) {
+            const int64_t v = vb + lane;
+            int64_t beg = 0, end = 0;
+            if (v <= v_last && active(v)) {
+                beg = max((long long)row_ptr[v], (long long)e_lo);
+                end = min((long long)row_ptr[v + 1], (long long)e_hi);
+            }
+            const int len = end > beg ? (int)(end - beg) : 0;
+            if (__builtin_amdgcn_ballot_w64(len > 0) == 0) continue;
+            if (!ptr) {
+                ptr = gpuvm_acquire(vm, page, false);
+                if (vm2) ptr2 = gpuvm_acquire(*vm2, page, false);
+            }
+            const bool small = len > 0 && len <= kSmall;
+            int longest = small ? len : 0;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) longest = max(longest, __shfl_xor(longest, off, 64));
+            const unsigned int my_off = (unsigned int)(beg - e_lo) << 2;
+            for (int j = 0; j < longest; ++j) {
+                if (small && j < len) {
+                    const unsigned int o = my_off + ((unsigned int)j << 2);
+                    visit(v, (int32_t)gpuvm_frame_load_b32(vm, ptr, o), o, ptr2);
+                }
+            }
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(len > kSmall);
+            while (todo) {
+                const unsigned int l = (unsigned int)__ffsll((long long)todo) - 1u;
+                todo &= todo - 1;
+                const unsigned int off0 = (unsigned int)__builtin_amdgcn_readlane((int)my_off, l);
+                const unsigned int n = (unsigned int)__builtin_amdgcn_readlane(len, l);
+                const int64_t vl = vb + l;
+                for (unsigned int i = lane; i < n; i += 64) {
+                    const unsigned int o = off0 + (i << 2);
+                    visit(vl, (int32_t)gpuvm_frame_load_b32(vm, ptr, o), o, ptr2);
+                }
+            }
+        }
+        if (ptr) {
+            gpuvm_release(vm, page);
+            if (vm2) gpuvm_release(*vm2, page);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
+                                                                const unsigned int *__restrict__ page_owner,
+                                                                int32_t *level, int32_t cur, int *changed) {
+    int found = 0;
+    walk_owned_pages(vm, nullptr, row_ptr, page_owner,
+                     [&](int64_t v) { return level[v] == cur; },
+                     [&](int64_t, int32_t u, unsigned int, const char *) {
+                         if (level[u] < 0) { level[u] = cur + 1; found = 1; }
+                     });
+    if (__builtin_amdgcn_ballot_w64(found != 0) && (threadIdx.x & 63) == 0) *changed = 1;
+}
+
+// Connected components (weak) by label propagation: every round walks every
+// edge (v, u) and pulls both labels down to the smaller one; the fixed point
+// labels each vertex with the smallest vertex id of its component.
+__global__ __launch_bounds__(kBlock) void k_cc_round_balanced(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
+                                                               const unsigned int *__restrict__ page_owner,
+                                                               int32_t *label, int *changed) {
+    int found = 0;
+    walk_owned_pages(vm, nullptr, row_ptr, page_owner,
+                     [&](int64_t) { return true; },
+                     [&](int64_t v, int32_t u, unsigned int, const char *) {
+                         const int32_t lv = __hip_atomic_load(label + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                         const int32_t lu = __hip_atomic_load(label + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                         if (lv < lu) {
+                             __hip_atomic_fetch_min(label + u, lv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                             found = 1;
+                         } else if (lu < lv) {
+                             __hip_atomic_fetch_min(label + v, lu, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                             found = 1;
+                         }
+                     });
+    if (__builtin_amdgcn_ballot_w64(found != 0) && (threadIdx.x & 63) == 0) *changed = 1;
+}
+
+// Single-source shortest paths, frontier-based Bellman-Ford: a round relaxes
+// the out-edges of the vertices whose distance fell in the previous round.
+// Edge weights are a second paged array with the layout of col_idx.
+__global__ __launch_bounds__(kBlock) void k_sssp_round_balanced(gpuvm_dev_t vm, gpuvm_dev_t vmw,
+                                                                 const int64_t *__restrict__ row_ptr,
+                                                                 const unsigned int *__restrict__ page_owner,
+                                                                 uint32_t *dist, const unsigned char *act_cur,
+                                                                 unsigned char *act_next, int *changed) {
+    int found = 0;
+    walk_owned_pages(vm, &vmw, row_ptr, page_owner,
+                     [&](int64_t v) { return act_cur[v] != 0; },
+                     [&](int64_t v, int32_t u, unsigned int off, const char *pw) {
+                         const uint32_t w = gpuvm_frame_load_b32(vmw, pw, off);
+                         const uint32_t dv = __hip_atomic_load(dist + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                         if (dv != 0xFFFFFFFFu) {
+                             const uint32_t nd = dv + w;
+                             const uint32_t old = __hip_atomic_fetch_min(dist + u, nd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                             if (nd < old) { act_next[u] = 1; found = 1; }
+                         }
+                     });
+    if (__builtin_amdgcn_ballot_w64(found != 0) && (threadIdx.x & 63) == 0) *changed = 1;
+}
+
+__global__ void k_iota32(int32_t *p, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = (int32_t)i;
+}
+
+extern "C" {
+
+static int ensure_page_owner(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, hipStream_t s);
+
+static int run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
+                   int *n_levels_out, void *stream, bool balanced) {
+    if (!vm || !d_row_ptr || !d_level || nv <= 0 || src < 0 || src >= nv || nv > 0x7FFFFFFF) return GPUVM_EINVAL;
+    if (vm->dev.bytes % 4) return GPUVM_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int waves = launch_waves(vm, balanced ? (size_t)vm->dev.n_pages : (size_t)((nv + 63) / 64));
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    if (balanced) {
+        int rc0 = ensure_page_owner(vm, d_row_ptr, nv, s);
+        if (rc0) return rc0;
+    }
+    k_fill32<<<1024, 256, 0, s>>>((unsigned int *)d_level, (size_t)nv, 0xFFFFFFFFu);
+    k_fill32<<<1, 64, 0, s>>>((unsigned int *)d_level + src, 1, 0u);
+    int levels = 0;
+    for (int32_t cur = 0;; ++cur) {
+        int changed = 0;
+        k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
+        if (balanced)
+            k_bfs_level_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, d_level,
+                                                                           cur, vm->bfs_changed);
+        else
+            k_bfs_level<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, nv, d_level, cur, vm->bfs_changed);
+        HIP_TRY(hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        ++levels;
+        if (!changed || cur == 0x7FFFFFFE) break;
+        int rc = check_kernel_error(vm);
+        if (rc) return rc;
+    }
+    if (n_levels_out) *n_levels_out = levels;
+    return check_kernel_error(vm);
+}
+
+int gpuvm_run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
+                  int *n_levels_out, void *stream) {
+    return run_bfs(vm, d_row_ptr, nv, src, d_level, n_levels_out, stream, false);
+}
+
+int gpuvm_run_bfs_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
+                           int *n_levels_out, void *stream) {
+    return run_bfs(vm, d_row_ptr, nv, src, d_level, n_levels_out, stream, true);
+}
+
+static int ensure_page_owner(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, hipStream_t s) {
+    if (!vm->page_owner) HIP_TRY(hipMalloc(&vm->page_owner, ((size_t)vm->dev.n_pages + 1) * sizeof(unsigned int)));
+    const unsigned int n = vm->dev.n_pages + 1;
+    k_bfs_page_owner<<<(n + 255) / 256, 256, 0, s>>>(d_row_ptr, nv, vm->dev.n_pages, vm->dev.page_shift - 2, vm->page_owner);
+    return GPUVM_OK;
+}
+
+int gpuvm_run_cc_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int32_t *d_label, int *n_rounds_out,
+                          void *stream) {
+    if (!vm || !d_row_ptr || !d_label || nv <= 0 || nv > 0x7FFFFFFF || vm->dev.bytes % 4) return GPUVM_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int waves = launch_waves(vm, vm->dev.n_pages);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    int rc = ensure_page_owner(vm, d_row_ptr, nv, s);
+    if (rc) return rc;
+    k_iota32<<<1024, 256, 0, s>>>(d_label, (size_t)nv);
+    int rounds = 0;
+    for (;;) {
+        int changed = 0;
+        k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
+        k_cc_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, d_label,
+                                                                      vm->bfs_changed);
+        HIP_TRY(hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        ++rounds;
+        rc = check_kernel_error(vm);
+        if (rc) return rc;
+        if (!changed || rounds > 1000000) break;
+    }
+    if (n_rounds_out) *n_rounds_out = rounds;
+    return GPUVM_OK;
+}
+
+int gpuvm_run_sssp_balanced(gpuvm_t *vm, gpuvm_t *vm_weights, const int64_t *d_row_ptr, int64_t nv, int64_t src,
+                            uint32_t *d_dist, int *n_rounds_out, void *stream) {
+    if (!vm || !vm_weights || vm == vm_weights || !d_row_ptr || !d_dist || nv <= 0 || nv > 0x7FFFFFFF || src < 0 ||
+        src >= nv)
+        return GPUVM_EINVAL;
+    if (vm->dev.bytes % 4 || vm_weights->dev.bytes != vm->dev.bytes || vm_weights->dev.page_shift != vm->dev.page_shift)
+        return GPUVM_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int waves = std::min(launch_waves(vm, vm->dev.n_pages), launch_waves(vm_weights, vm->dev.n_pages));
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    int rc = ensure_page_owner(vm, d_row_ptr, nv, s);
+    if (rc) return rc;
+    unsigned char *act = nullptr;                           // two activity maps, swapped every round
+    HIP_TRY(hipMalloc(&act, 2 * (size_t)nv));
+    k_fill8<<<1024, 256, 0, s>>>(act, 2 * (size_t)nv, 0);
+    k_fill8<<<1, 64, 0, s>>>(act + src, 1, 1);
+    k_fill32<<<1024, 256, 0, s>>>(d_dist, (size_t)nv, 0xFFFFFFFFu);
+    k_fill32<<<1, 64, 0, s>>>(d_dist + src, 1, 0u);
+    int rounds = 0;
+    rc = GPUVM_OK;
+    for (;;) {
+        int changed = 0;
+        unsigned char *cur = act + (size_t)(rounds & 1) * nv, *next = act + (size_t)((rounds + 1) & 1) * nv;
+        k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
+        k_fill8<<<1024, 256, 0, s>>>(next, (size_t)nv, 0);
+        k_sssp_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, vm_weights->dev, d_row_ptr,
+                                                                        vm->page_owner, d_dist, cur, next,
+                                                                        vm->bfs_changed);
+        hipError_t e = hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) { rc = GPUVM_EHIP; break; }
+        ++rounds;
+        rc = check_kernel_error(vm);
+        if (!rc) rc = check_kernel_error(vm_weights);
+        if (rc || !changed || rounds > 1000000) break;
+    }
+    (void)hipFree(act);
+    if (n_rounds_out) *n_rounds_out = rounds;
+    return rc;
+}
+
+}  // extern "C"

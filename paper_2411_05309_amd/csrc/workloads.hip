@@ -1,0 +1,302 @@
+// libgpuvm - kernels and launchers of the array workloads: random gather, scatter-increment, vector addition, streaming reduce, embedding bag, column-order product, filter-then-gather.
+// The fault path itself (page-table lookup, wavefront dedup, frame allocation,
+// eviction, write-back, migration) is in include/gpuvm_device.h and is inlined
+// into every kernel, the way the paper inlines its runtime into the application
+// kernels (System Overview; Register usage).
+#include "gpuvm_internal.h"
+
+using namespace gpuvm_detail;
+
+// Random gather: one access per lane per iteration, grid-stride.
+__global__ __launch_bounds__(kBlock) void k_gather(gpuvm_dev_t vm, const uint32_t *__restrict__ idx, size_t n,
+                                                    uint32_t *__restrict__ out, unsigned long long *sum,
+                                                    unsigned long long n_elems) {
+    const size_t nthreads = (size_t)gridDim.x * kBlock;
+    unsigned long long acc = 0;
+    const size_t n_up = (n + 63) & ~(size_t)63;                  // whole waves iterate together
+    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n_up; k += nthreads) {
+        unsigned long long i = k < n ? idx[k] : 0;
+        bool want = k < n;
+        if (want && i >= n_elems) { raise_error(vm, GPUVM_ERANGE); want = false; }
+        const uint32_t v = gpuvm_load_if<uint32_t>(vm, i, want);
+        if (want) { out[k] = v; acc += v; }
+    }
+    if (sum) {
+        // every lane of the wave reaches this point (the loop has ended for all)
+        acc = wave_sum(acc);
+        if ((threadIdx.x & 63) == 0 && acc)
+            __hip_atomic_fetch_add(sum, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Scatter-increment: data[idx[k]] += 1 through the paged view.
+__global__ __launch_bounds__(kBlock) void k_scatter_inc(gpuvm_dev_t vm, const uint32_t *__restrict__ idx, size_t n,
+                                                         unsigned long long n_elems) {
+    const size_t nthreads = (size_t)gridDim.x * kBlock;
+    const size_t n_up = (n + 63) & ~(size_t)63;
+    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n_up; k += nthreads) {
+        unsigned long long i = k < n ? idx[k] : 0;
+        bool want = k < n;
+        if (want && i >= n_elems) { raise_error(vm, GPUVM_ERANGE); want = false; }
+        gpuvm_atomic_add_if<unsigned long long>(vm, i, 1ull, want);
+    }
+}
+
+// The paper's own example (vector-addition listing): C[i] = A[i] + B[i] with all
+// three vectors paged; C is written through gpuvm_store, so its pages become
+// DIRTY and are written back at eviction or flush.
+// Work distribution: a wave takes one page-sized stripe of the index range at a
+// time (consecutive stripes to consecutive waves), so that the waves in flight
+// fault on different pages; with a plain grid-stride loop all of them would
+// stand on the same handful of pages and wait for one fetch at a time.
+__global__ __launch_bounds__(kBlock) void k_vector_add(gpuvm_dev_t a, gpuvm_dev_t b, gpuvm_dev_t c, size_t n) {
+    const unsigned int lane = threadIdx.x & 63;
+    const size_t wave = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
+    const size_t stripe = (size_t)1 << (c.page_shift - 2);               // floats per page of C
+    for (size_t lo = wave * stripe; lo < n; lo += nwaves * stripe) {
+        const size_t hi = lo + stripe < n ? lo + stripe : n;
+        for (size_t i0 = lo; i0 < hi; i0 += 64) {
+            const size_t i = i0 + lane;
+            const bool want = i < hi;
+            const float x = gpuvm_load_if<float>(a, want ? i : 0, want);
+            const float y = gpuvm_load_if<float>(b, want ? i : 0, want);
+            gpuvm_store_if<float>(c, want ? i : 0, x + y, want);
+        }
+    }
+}
+
+// Streaming read-reduce: wave w takes pages w, w + nwaves, ...; the page's
+// floats are summed in fp64 and added to the sum of the block it belongs to.
+__global__ __launch_bounds__(kBlock) void k_stream_reduce(gpuvm_dev_t vm, unsigned int pages_per_block,
+                                                           double *sums) {
+    const unsigned int lane = threadIdx.x & 63;
+    const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const unsigned int nwaves = (gridDim.x * kBlock) >> 6;
+    for (unsigned int page = wave; page < vm.n_pages; page += nwaves) {
+        const unsigned int len = page_len(vm, page);
+        const unsigned int nvec = len >> 4;                           // float4 items
+        const char *p = gpuvm_acquire(vm, page, false);
+        double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+        for (unsigned int i = lane; i < nvec; i += 64) {
+            const u32x4 v = gpuvm_frame_load_b128(vm, p, i << 4);
+            a0 += (double)__uint_as_float(v.x); a1 += (double)__uint_as_float(v.y);
+            a2 += (double)__uint_as_float(v.z); a3 += (double)__uint_as_float(v.w);
+        }
+        // floats beyond the last full float4 of a short last page
+        if ((nvec << 4) + (lane << 2) < len)
+            a0 += (double)__uint_as_float(gpuvm_frame_load_b32(vm, p, (nvec << 4) + (lane << 2)));
+        gpuvm_release(vm, page);
+        double s = (a0 + a1) + (a2 + a3);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+        if (lane == 0)
+            __hip_atomic_fetch_add(sums + page / pages_per_block, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Embedding bag, sum pooling: one wave per bag; a row of 64*VPL floats is read
+// as VPL consecutive floats per lane; rows are added in listed order in fp32.
+template <int VPL>
+__global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const int32_t *__restrict__ ids,
+                                                           size_t bags, unsigned int bag_len, float *__restrict__ out,
+                                                           unsigned long long n_rows) {
+    typedef float vec_t __attribute__((ext_vector_type(VPL)));
+    const unsigned int lane = threadIdx.x & 63;
+    const size_t wave = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
+    const unsigned int row_bytes = 64u * VPL * 4u;
+    for (size_t bag = wave; bag < bags; bag += nwaves) {
+        vec_t acc = 0.0f;
+        for (unsigned int j0 = 0; j0 < bag_len; j0 += 64) {
+            const unsigned int nj = min(64u, bag_len - j0);
+            int my_id = 0;
+            if (lane < nj) my_id = ids[bag * bag_len + j0 + lane];
+            for (unsigned int j = 0; j < nj; ++j) {
+                const unsigned long long id = (unsigned int)__builtin_amdgcn_readlane(my_id, j);
+                if (id >= n_rows) { if (lane == 0) raise_error(vm, GPUVM_ERANGE); continue; }
+                const unsigned long long byte = id * row_bytes;
+                const unsigned int page = (unsigned int)(byte >> vm.page_shift);
+                const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
+                const char *p = gpuvm_acquire(vm, page, false);
+                vec_t v;
+                const unsigned int o = off + lane * (VPL * 4u);
+                if constexpr (VPL == 1) {
+                    v = __uint_as_float(gpuvm_frame_load_b32(vm, p, o));
+                } else if constexpr (VPL == 2) {
+                    const u32x2 r = gpuvm_frame_load_b64(vm, p, o);
+                    v.x = __uint_as_float(r.x); v.y = __uint_as_float(r.y);
+                } else {
+                    const u32x4 r = gpuvm_frame_load_b128(vm, p, o);
+                    v.x = __uint_as_float(r.x); v.y = __uint_as_float(r.y);
+                    v.z = __uint_as_float(r.z); v.w = __uint_as_float(r.w);
+                }
+                gpuvm_release(vm, page);
+                acc += v;
+            }
+        }
+        *reinterpret_cast<vec_t *>(out + bag * (64u * VPL) + lane * VPL) = acc;
+    }
+}
+
+// Transposed matrix-vector product y = A^T x over a paged row-major fp32 matrix:
+// a thread owns a column and walks down the rows, so consecutive accesses of a
+// thread are a whole row apart (the column-order pattern of the paper's
+// transfer-bound applications, which has no spatial locality per thread); the
+// 64 lanes of a wave read 256 consecutive bytes of one row.  fp64 accumulation.
+__global__ __launch_bounds__(kBlock) void k_matvec_t(gpuvm_dev_t vm, unsigned long long rows, unsigned long long cols,
+                                                      unsigned int skew, const float *__restrict__ x,
+                                                      double *__restrict__ y) {
+    const size_t nthreads = (size_t)gridDim.x * kBlock;
+    const unsigned long long cols_up = (cols + 63) & ~63ull;           // whole waves stay together
+    for (unsigned long long j = (size_t)blockIdx.x * kBlock + threadIdx.x; j < cols_up; j += nthreads) {
+        double acc = 0.0;
+        const bool want = j < cols;
+        // Waves that walk down the same rows in lock step would all wait for
+        // the same one or two pages at a time; starting each block of columns
+        // a few rows apart keeps `skew` rows of pages in flight instead.
+        const unsigned long long r0 = (j >> 6) % skew;
+        for (unsigned long long k = 0; k < rows; ++k) {
+            const unsigned long long i = k + r0 < rows ? k + r0 : k + r0 - rows;
+            acc += (double)gpuvm_load_if<float>(vm, want ? i * cols + j : 0, want) * (double)x[i];
+        }
+        if (want) y[j] = acc;
+    }
+}
+
+// Filter-then-gather over two paged uint32 columns (the paper's query pattern:
+// scan one column, fetch another only for the few rows that pass): for rows
+// with key > threshold add val[row] to a 64-bit sum and count the row.  The key
+// column is streamed page by page by whole waves; the value column is reached
+// through the element accessor by the (sparse, divergent) matching lanes.
+__global__ __launch_bounds__(kBlock) void k_filter_sum(gpuvm_dev_t vmk, gpuvm_dev_t vmv, unsigned int threshold,
+                                                        unsigned long long *count, unsigned long long *sum) {
+    const unsigned int lane = threadIdx.x & 63;
+    const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const unsigned int nwaves = (gridDim.x * kBlock) >> 6;
+    const unsigned int elems_shift = vmk.page_shift - 2;
+    unsigned long long my_count = 0, my_sum = 0;
+    for (unsigned int page = wave; page < vmk.n_pages; page += nwaves) {
+        const unsigned int n = page_len(vmk, page) >> 2;
+        const unsigned long long first = (unsigned long long)page << elems_shift;
+        const char *p = gpuvm_acquire(vmk, page, false);
+        for (unsigned int i0 = 0; i0 < n; i0 += 64) {
+            const unsigned int i = i0 + lane;
+            const bool hit = i < n && gpuvm_frame_load_b32(vmk, p, i << 2) > threshold;
+            if (__builtin_amdgcn_ballot_w64(hit) == 0) continue;
+            const uint32_t v = gpuvm_load_if<uint32_t>(vmv, hit ? first + i : 0, hit);   // all lanes help to fault
+            if (hit) {
+                my_sum += v;
+                my_count += 1;
+            }
+        }
+        gpuvm_release(vmk, page);
+    }
+    my_sum = wave_sum(my_sum);
+    my_count = wave_sum(my_count);
+    if (lane == 0 && my_count) {
+        __hip_atomic_fetch_add(sum, my_sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(count, my_count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+extern "C" {
+
+int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n, uint32_t *d_out, uint64_t *d_sum,
+                     void *stream) {
+    if (!vm || (n && (!d_idx || !d_out))) return GPUVM_EINVAL;
+    if (n == 0) return GPUVM_OK;
+    const int waves = launch_waves(vm, (n + 63) / 64);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    k_gather<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, d_out,
+                                                                         (unsigned long long *)d_sum,
+                                                                         vm->dev.bytes / 4);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_scatter_increment(gpuvm_t *vm, const uint32_t *d_idx, size_t n, void *stream) {
+    if (!vm || (n && !d_idx)) return GPUVM_EINVAL;
+    if (n == 0) return GPUVM_OK;
+    const int waves = launch_waves(vm, (n + 63) / 64);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    k_scatter_inc<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, vm->dev.bytes / 8);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n, void *stream) {
+    if (!vm_a || !vm_b || !vm_c || vm_a == vm_c || vm_b == vm_c) return GPUVM_EINVAL;
+    if (n * 4 > vm_a->dev.bytes || n * 4 > vm_b->dev.bytes || n * 4 > vm_c->dev.bytes) return GPUVM_ERANGE;
+    if (n == 0) return GPUVM_OK;
+    const size_t work = (n * 4 + vm_c->page_bytes - 1) / vm_c->page_bytes;       // page-sized stripes
+    const int waves = std::min({launch_waves(vm_a, work), launch_waves(vm_b, work), launch_waves(vm_c, work)});
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    k_vector_add<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, vm_c->dev, n);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_stream_reduce(gpuvm_t *vm, size_t block_elems, double *d_sums, void *stream) {
+    if (!vm || !d_sums || block_elems == 0) return GPUVM_EINVAL;
+    const size_t block_bytes = block_elems * 4;
+    if (block_bytes % vm->page_bytes || vm->dev.bytes % 4) return GPUVM_EINVAL;
+    const unsigned int ppb = (unsigned int)(block_bytes / vm->page_bytes);
+    const size_t nblocks = (vm->dev.n_pages + ppb - 1) / ppb;
+    const int waves = launch_waves(vm, vm->dev.n_pages);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    hipStream_t s = (hipStream_t)stream;
+    k_fill64<<<64, 256, 0, s>>>((unsigned long long *)d_sums, nblocks, 0ull);   // +0.0
+    k_stream_reduce<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, ppb, d_sums);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids, size_t bags, size_t bag_len,
+                            float *d_out, void *stream) {
+    if (!vm || !d_ids || !d_out || bag_len == 0 || bag_len > 0xFFFFFFFFu) return GPUVM_EINVAL;
+    if (dim != 64 && dim != 128 && dim != 256) return GPUVM_EINVAL;
+    const size_t row_bytes = dim * 4;
+    if (vm->page_bytes % row_bytes || vm->dev.bytes % row_bytes) return GPUVM_EINVAL;
+    if (bags == 0) return GPUVM_OK;
+    const int waves = launch_waves(vm, bags);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    const int grid = grid_for_waves(waves);
+    hipStream_t s = (hipStream_t)stream;
+    const unsigned long long n_rows = vm->dev.bytes / row_bytes;
+    if (dim == 64) k_embedding_bag<1><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, (unsigned int)bag_len, d_out, n_rows);
+    else if (dim == 128) k_embedding_bag<2><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, (unsigned int)bag_len, d_out, n_rows);
+    else k_embedding_bag<4><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, (unsigned int)bag_len, d_out, n_rows);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, double *d_y, void *stream) {
+    if (!vm || !d_x || !d_y || rows == 0 || cols == 0) return GPUVM_EINVAL;
+    if (rows * cols * 4 != vm->dev.bytes) return GPUVM_EINVAL;
+    const int waves = launch_waves(vm, (cols + 63) / 64);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    // rows of A the pool can hold; the start rows are spread over a window well inside it
+    const size_t rows_in_pool = (size_t)vm->dev.n_frames * vm->page_bytes / (cols * 4);
+    const unsigned int skew = (unsigned int)std::max<size_t>(1, std::min<size_t>({(size_t)64, rows_in_pool / 4, rows}));
+    k_matvec_t<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, skew, d_x, d_y);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_filter_sum(gpuvm_t *vm_key, gpuvm_t *vm_val, uint32_t threshold, uint64_t *d_count, uint64_t *d_sum,
+                         void *stream) {
+    if (!vm_key || !vm_val || vm_key == vm_val || !d_count || !d_sum) return GPUVM_EINVAL;
+    if (vm_key->dev.bytes % 4 || vm_val->dev.bytes != vm_key->dev.bytes) return GPUVM_EINVAL;
+    const int waves = std::min(launch_waves(vm_key, vm_key->dev.n_pages), launch_waves(vm_val, vm_key->dev.n_pages));
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    hipStream_t s = (hipStream_t)stream;
+    k_fill64<<<1, 64, 0, s>>>((unsigned long long *)d_count, 1, 0ull);
+    k_fill64<<<1, 64, 0, s>>>((unsigned long long *)d_sum, 1, 0ull);
+    k_filter_sum<<<grid_for_waves(waves), kBlock, 0, s>>>(vm_key->dev, vm_val->dev, threshold,
+                                                          (unsigned long long *)d_count, (unsigned long long *)d_sum);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+}  // extern "C"
