@@ -145,7 +145,7 @@ int gpuvm_destroy(gpuvm_t *vm) {
     gpuvm_dev_t &d = vm->dev;
     (void)hipFree(d.frames); (void)hipFree(d.pte); (void)hipFree(d.frame_owner); (void)hipFree(d.hand); (void)hipFree(d.stats);
     (void)hipFree(vm->stamp); (void)hipFree(vm->first); (void)hipFree(vm->miss); (void)hipFree(vm->miss_sorted); (void)hipFree(vm->jobs);
-    (void)hipFree(vm->phase_ctr); (void)hipFree(vm->bfs_changed); (void)hipFree(vm->page_owner);
+    (void)hipFree(vm->phase_ctr); (void)hipFree(vm->bfs_changed); (void)hipFree(vm->page_owner); (void)hipFree(vm->row_progress);
     delete vm;
     return GPUVM_OK;
 }

@@ -39,6 +39,7 @@ struct gpuvm {
     unsigned int phase_tag = 0;
     int *bfs_changed = nullptr;
     unsigned int *page_owner = nullptr;   // [n_pages + 1], edge-balanced BFS
+    unsigned int *row_progress = nullptr; // [8192] row reached by each compute wave (column-order product)
 };
 
 #define HIP_TRY(expr)                                                            \

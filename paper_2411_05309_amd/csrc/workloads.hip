@@ -144,23 +144,75 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
 // thread are a whole row apart (the column-order pattern of the paper's
 // transfer-bound applications, which has no spatial locality per thread); the
 // 64 lanes of a wave read 256 consecutive bytes of one row.  fp64 accumulation.
+//
+// Every page is wanted by all the waves whose columns lie in it, each at the
+// moment it reaches that row.  Two things keep this from degenerating:
+//  - fault-ahead helpers (the first `helper_blocks` workgroups) touch the pages
+//    of the rows to come (acquire, release) in parallel, so that the compute
+//    waves find them resident instead of fetching them one after the other;
+//  - a sliding window: every compute wave publishes the row it has reached in
+//    progress[wave]; nobody - helper or compute wave - goes further than
+//    `window` rows beyond the slowest compute wave.  Without it a wave that
+//    falls behind by more than the pool holds finds its pages evicted, has to
+//    fetch every one itself and falls further behind (measured: 2-3x the
+//    traffic, 8x the time).  The slowest wave is never held back, so the
+//    window always moves; waiting is bounded by spin_limit all the same.
+__device__ __forceinline__ unsigned int slowest_row(const unsigned int *progress, unsigned int n_compute_waves) {
+    unsigned int lo = 0xFFFFFFFFu;
+    for (unsigned int i = threadIdx.x & 63; i < n_compute_waves; i += 64) lo = min(lo, a_load(progress + i));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) lo = min(lo, (unsigned int)__shfl_xor((int)lo, off, 64));
+    return lo;
+}
+
 __global__ __launch_bounds__(kBlock) void k_matvec_t(gpuvm_dev_t vm, unsigned long long rows, unsigned long long cols,
-                                                      unsigned int skew, const float *__restrict__ x,
-                                                      double *__restrict__ y) {
-    const size_t nthreads = (size_t)gridDim.x * kBlock;
+                                                      unsigned int skew, unsigned int helper_blocks,
+                                                      unsigned int window, unsigned int *progress,
+                                                      const float *__restrict__ x, double *__restrict__ y) {
+    const unsigned int lane = threadIdx.x & 63;
+    const unsigned int n_compute_waves = ((gridDim.x - helper_blocks) * kBlock) >> 6;
+    if (blockIdx.x < helper_blocks) {
+        const unsigned int hw = (blockIdx.x * kBlock + threadIdx.x) >> 6;
+        const unsigned int nh = (helper_blocks * kBlock) >> 6;
+        const unsigned long long row_bytes = cols * 4;
+        unsigned int at = 0;
+        for (unsigned int page = hw; page < vm.n_pages; page += nh) {
+            const unsigned long long row = ((unsigned long long)page << vm.page_shift) / row_bytes;
+            for (unsigned int polls = 0; row > (unsigned long long)at + window && polls < vm.spin_limit; ++polls) {
+                at = slowest_row(progress, n_compute_waves);
+                if (row <= (unsigned long long)at + window || ((polls & 255) == 255 && aborted(vm))) break;
+                __builtin_amdgcn_s_sleep(32);
+            }
+            if (row + skew < at) continue;                    // every compute wave is already past it
+            gpuvm_acquire(vm, page, false);
+            gpuvm_release(vm, page);
+        }
+        return;
+    }
+    const unsigned int cwave = ((blockIdx.x - helper_blocks) * kBlock + threadIdx.x) >> 6;
+    const size_t nthreads = (size_t)(gridDim.x - helper_blocks) * kBlock;
     const unsigned long long cols_up = (cols + 63) & ~63ull;           // whole waves stay together
-    for (unsigned long long j = (size_t)blockIdx.x * kBlock + threadIdx.x; j < cols_up; j += nthreads) {
+    for (unsigned long long j = (size_t)(blockIdx.x - helper_blocks) * kBlock + threadIdx.x; j < cols_up; j += nthreads) {
         double acc = 0.0;
         const bool want = j < cols;
-        // Waves that walk down the same rows in lock step would all wait for
-        // the same one or two pages at a time; starting each block of columns
-        // a few rows apart keeps `skew` rows of pages in flight instead.
+        // a small spread of the start rows keeps the compute waves from hitting
+        // one page word all at the same instant
         const unsigned long long r0 = (j >> 6) % skew;
+        unsigned int slowest = 0;
         for (unsigned long long k = 0; k < rows; ++k) {
             const unsigned long long i = k + r0 < rows ? k + r0 : k + r0 - rows;
+            if (window && (k & 15) == 0) {
+                if (lane == 0) a_store(progress + cwave, (unsigned int)k);
+                for (unsigned int polls = 0; k > (unsigned long long)slowest + window / 2 && polls < vm.spin_limit; ++polls) {
+                    slowest = slowest_row(progress, n_compute_waves);
+                    if (k <= (unsigned long long)slowest + window / 2 || ((polls & 255) == 255 && aborted(vm))) break;
+                    __builtin_amdgcn_s_sleep(32);
+                }
+            }
             acc += (double)gpuvm_load_if<float>(vm, want ? i * cols + j : 0, want) * (double)x[i];
         }
         if (want) y[j] = acc;
+        if (window && lane == 0) a_store(progress + cwave, 0xFFFFFFF0u);   // done: never the slowest again
     }
 }
 
@@ -274,12 +326,24 @@ int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids, size_
 int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, double *d_y, void *stream) {
     if (!vm || !d_x || !d_y || rows == 0 || cols == 0) return GPUVM_EINVAL;
     if (rows * cols * 4 != vm->dev.bytes) return GPUVM_EINVAL;
+    if (rows >= 0xFFFFFFF0ull) return GPUVM_EINVAL;
+    const int cap = launch_waves(vm, (size_t)1 << 40);
     const int waves = launch_waves(vm, (cols + 63) / 64);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
-    // rows of A the pool can hold; the start rows are spread over a window well inside it
+    // rows of A the pool can hold; start rows, the helpers' lead and the spread of
+    // the compute waves all stay well inside it
     const size_t rows_in_pool = (size_t)vm->dev.n_frames * vm->page_bytes / (cols * 4);
     const unsigned int skew = (unsigned int)std::max<size_t>(1, std::min<size_t>({(size_t)64, rows_in_pool / 4, rows}));
-    k_matvec_t<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, skew, d_x, d_y);
+    // one pass over the rows per wave is what the window reasons about
+    const bool single_pass = (size_t)waves * 64 >= cols;
+    const unsigned int window = single_pass && rows_in_pool >= 16 ? (unsigned int)std::min<size_t>(rows_in_pool / 2, 0x7FFFFFFF) : 0;
+    // fault-ahead helpers: what is left of the wave budget, at most two per compute unit
+    const int helpers = window ? std::min(cap - waves, vm->cus * 2) / kWavesPerBlock * kWavesPerBlock : 0;
+    hipStream_t s = (hipStream_t)stream;
+    if (!vm->row_progress) HIP_TRY(hipMalloc(&vm->row_progress, 8192 * sizeof(unsigned int)));
+    k_fill32<<<8, 256, 0, s>>>(vm->row_progress, 8192, 0u);
+    k_matvec_t<<<grid_for_waves(waves) + helpers / kWavesPerBlock, kBlock, 0, s>>>(
+        vm->dev, rows, cols, skew, (unsigned int)(helpers / kWavesPerBlock), window, vm->row_progress, d_x, d_y);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }
