@@ -102,9 +102,12 @@ int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_p
     gpuvm_t *vm = new (std::nothrow) gpuvm();
     if (!vm) return GPUVM_ENOMEM;
     memset(&vm->dev, 0, sizeof(vm->dev));
-    HIP_TRY(hipGetDevice(&vm->device));
     hipDeviceProp_t prop;
-    HIP_TRY(hipGetDeviceProperties(&prop, vm->device));
+    if (hipGetDevice(&vm->device) != hipSuccess || hipGetDeviceProperties(&prop, vm->device) != hipSuccess) {
+        (void)hipGetLastError();
+        delete vm;
+        return GPUVM_EHIP;
+    }
     vm->cus = prop.multiProcessorCount;
     vm->waves_per_cu = 8;
     if (const char *e = getenv("GPUVM_WAVES_PER_CU")) vm->waves_per_cu = std::max(1, std::min(32, atoi(e)));

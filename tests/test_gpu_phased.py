@@ -102,3 +102,24 @@ def test_phase_with_more_pages_than_frames_is_refused(gpu):
         with pytest.raises(gv.GpuvmError) as e:
             gv.gpuvm_run_gather_phased(b.vm, dev(idx), 32, 32, d_out, None)
         assert e.value.code == gv.EDEADLK
+
+
+def test_gather_phased_full_size_config(gpu):
+    """The headline configuration (64 MiB, 4 KiB pages, 4096 frames, 2^20 uniform
+    indices) in phases of 1024 accesses: counts, cursor and the final frame
+    table equal the sequential CLOCK replay."""
+    n_elems, n_idx, page, frames, phase_len = 1 << 24, 1 << 20, 4096, 4096, 1024
+    data = inputs.u32_values(0x9E3779B9, 0, n_elems)
+    idx = inputs.u32_indices(1, 0, n_idx, n_elems)
+    want, want_sum = oracle.gather(data, idx)
+    sim = oracle.PagingSim(page // 8, frames, oracle.CLOCK, n_words=data.nbytes // 8)
+    sim.run((idx.astype(np.uint64) * 4) // 8, phase_len=phase_len)
+    # independent-reference sanity: ~3/4 of the distinct pages of a phase miss
+    assert 0.7 * n_idx < sim.counters["faults"] < 0.8 * n_idx
+    with Backing(data, page, frames * page, gv.POLICY_CLOCK) as b:
+        d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
+        d_sum = torch.zeros(1, dtype=torch.int64, device="cuda")
+        gv.gpuvm_run_gather_phased(b.vm, dev(idx), n_idx, phase_len, d_out, d_sum)
+        assert np.array_equal(host(d_out, np.uint32), want)
+        assert int(host(d_sum, np.uint64)[0]) == want_sum
+        _compare_with_replay(b, sim, frames)
