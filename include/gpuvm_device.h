@@ -372,6 +372,45 @@ __device__ __forceinline__ void gpuvm_release(const gpuvm_dev_t &vm, unsigned in
     if (w.leader) a_add(vm.pte + page, ~0ull);                /* pin - 1 */
 }
 
+/* Optimistic page-level read for wave-level users (same page in every lane):
+ * gpuvm_peek returns the frame of `page` if it is RESIDENT right now, without
+ * taking a reference, and the page's word in *token; read the frame with
+ * gpuvm_frame_load_*(), then ask gpuvm_peek_valid: true means the frame held
+ * the page during all of those reads (state, frame and install generation are
+ * unchanged), false means the values must be thrown away and the page taken
+ * with gpuvm_acquire.  Nothing is pinned, so readers of a hot page do not
+ * serialise on its word and never hold up an eviction. */
+__device__ __forceinline__ const char *gpuvm_peek(const gpuvm_dev_t &vm, unsigned int page_any,
+                                                  unsigned long long *token) {
+    using namespace gpuvm_detail;
+    const wave_t w = wave_now();
+    const unsigned int page = bcast(page_any);
+    unsigned long long word = 0;
+    if (w.leader) word = a_load(vm.pte + page);
+    word = bcast(word);
+    *token = word;
+    if (((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT) return nullptr;
+    return vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift);
+}
+__device__ __forceinline__ bool gpuvm_peek_valid(const gpuvm_dev_t &vm, unsigned int page_any,
+                                                 unsigned long long token) {
+    using namespace gpuvm_detail;
+    const wave_t w = wave_now();
+    const unsigned int page = bcast(page_any);
+    wait_vm();                                                /* the reads have returned */
+    unsigned int same = 0;
+    if (w.leader) {
+        const unsigned long long again = a_load(vm.pte + page);
+        same = ((again ^ token) & GPUVM_PTE_IDENT_MASK) == 0;
+        if (same && vm.policy == GPUVM_POLICY_CLOCK && !(again & GPUVM_PTE_REF)) {
+            unsigned long long expect = again;                /* second-chance bit, best effort */
+            a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
+        }
+        if (same && (vm.flags & GPUVM_F_ACCESS_STATS)) stat_add(vm, GPUVM_S_HITS, 1);
+    }
+    return bcast(same) != 0;
+}
+
 /* Coherent reads of frame memory for wave-level users of gpuvm_acquire:
  * `frame` is the pointer gpuvm_acquire returned (the same in every lane),
  * `byte_off` the lane's offset into the page.  Offsets beyond the page read 0. */

@@ -118,20 +118,36 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
                 const unsigned long long byte = id * row_bytes;
                 const unsigned int page = (unsigned int)(byte >> vm.page_shift);
                 const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
-                const char *p = gpuvm_acquire(vm, page, false);
-                vec_t v;
                 const unsigned int o = off + lane * (VPL * 4u);
-                if constexpr (VPL == 1) {
-                    v = __uint_as_float(gpuvm_frame_load_b32(vm, p, o));
-                } else if constexpr (VPL == 2) {
-                    const u32x2 r = gpuvm_frame_load_b64(vm, p, o);
-                    v.x = __uint_as_float(r.x); v.y = __uint_as_float(r.y);
-                } else {
-                    const u32x4 r = gpuvm_frame_load_b128(vm, p, o);
-                    v.x = __uint_as_float(r.x); v.y = __uint_as_float(r.y);
-                    v.z = __uint_as_float(r.z); v.w = __uint_as_float(r.w);
+                auto load_row = [&](const char *p) {
+                    vec_t r4;
+                    if constexpr (VPL == 1) {
+                        r4 = __uint_as_float(gpuvm_frame_load_b32(vm, p, o));
+                    } else if constexpr (VPL == 2) {
+                        const u32x2 r = gpuvm_frame_load_b64(vm, p, o);
+                        r4.x = __uint_as_float(r.x); r4.y = __uint_as_float(r.y);
+                    } else {
+                        const u32x4 r = gpuvm_frame_load_b128(vm, p, o);
+                        r4.x = __uint_as_float(r.x); r4.y = __uint_as_float(r.y);
+                        r4.z = __uint_as_float(r.z); r4.w = __uint_as_float(r.w);
+                    }
+                    return r4;
+                };
+                // hot rows are read without a reference; a miss (or a page that
+                // left meanwhile) goes through the pinned path
+                vec_t v;
+                unsigned long long token;
+                const char *p = gpuvm_peek(vm, page, &token);
+                bool ok = false;
+                if (p) {
+                    v = load_row(p);
+                    ok = gpuvm_peek_valid(vm, page, token);
                 }
-                gpuvm_release(vm, page);
+                if (!ok) {
+                    p = gpuvm_acquire(vm, page, false);
+                    v = load_row(p);
+                    gpuvm_release(vm, page);
+                }
                 acc += v;
             }
         }
