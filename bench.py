@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
-    ap.add_argument("--sweep", default=None, choices=["oversubscription", "page_size"],
+    ap.add_argument("--sweep", default=None, choices=["oversubscription", "page_size", "policy"],
                     help="instead of the benchmark line: one JSON line per point of a sweep")
     return ap.parse_args()
 
@@ -762,6 +762,52 @@ def sweep_page_size(gv, torch, np, inputs, oracle):
     gv.free_pinned(garr)
 
 
+def sweep_policy(gv, torch, np, inputs, oracle):
+    """The four eviction policies on a workload that mixes written and read-only
+    pages (paper: Comparisons with UVM - write-intensive pages could be kept
+    longer than read-intensive ones): a 1 GiB uint64 array, 64 KiB pages, 256 MiB
+    pool (4096 frames).  The first eighth of the array is the write region (2048
+    pages) in four slices; round r adds 2^16 increments to slice r mod 4 and then
+    gathers 512 uniform uint32 elements from the whole array (about 450 faults),
+    so a written page is written again a few thousand ring positions later -
+    between the second and the third visit of the hand; 256 rounds, then flush.  Checked against the same
+    sequence on plain memory."""
+    n64, page, pool, rounds, per, reads, slices = 1 << 27, 65536, 256 << 20, 256, 1 << 16, 512, 4
+    slice_elems = (n64 >> 3) // slices
+    w_idx = [(inputs.u32_indices(100 + r, 0, per, slice_elems) + np.uint32((r % slices) * slice_elems)) for r in range(rounds)]
+    r_idx = [inputs.u32_indices(200 + r, 0, reads, n64 << 1) for r in range(rounds)]
+    ref = np.zeros(n64, np.uint64)
+    want = []
+    for r in range(rounds):                                   # the definition, on plain memory
+        oracle.scatter_increment(ref, w_idx[r])
+        want.append(oracle.gather(ref.view(np.uint32), r_idx[r])[0])
+    arr = gv.pinned_array((n64,), np.uint64)
+    d_w = [torch.from_numpy(x.view(np.int32)).cuda() for x in w_idx]
+    d_r = [torch.from_numpy(x.view(np.int32)).cuda() for x in r_idx]
+    d_out = torch.zeros((rounds, reads), dtype=torch.int32, device="cuda")
+    for name, pol in (("fifo", gv.POLICY_FIFO), ("fifo_wait", gv.POLICY_FIFO_WAIT), ("clock", gv.POLICY_CLOCK),
+                      ("clock_write_aware", gv.POLICY_CLOCK_WRITE_AWARE)):
+        arr[...] = 0
+        vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, pool, pol)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r in range(rounds):
+            gv.gpuvm_run_scatter_increment(vm, d_w[r], per)
+            gv.gpuvm_run_gather(vm, d_r[r], reads, d_out[r], None)
+        gv.gpuvm_flush(vm)
+        ms = (time.perf_counter() - t0) * 1e3
+        st = gv.gpuvm_stats(vm)
+        got = d_out.cpu().numpy().view(np.uint32)
+        ok = bool(np.array_equal(arr, ref)) and all(bool(np.array_equal(got[r], want[r])) for r in range(rounds))
+        print(json.dumps({"sweep": "policy", "workload": "rotating_increments_and_sparse_gathers_1GiB_u64_64KiB_pages_256MiB_pool",
+                          "policy": name, "ms": round(ms, 2), "faults": st["faults"],
+                          "writebacks_evict": st["writebacks_evict"], "writebacks_flush": st["writebacks_flush"],
+                          "link_in_GB": round(st["bytes_in"] / 1e9, 3), "link_out_GB": round(st["bytes_out"] / 1e9, 3),
+                          "alloc_skips": st["alloc_skips"], "alloc_sweeps": st["alloc_sweeps"], "parity": ok}), flush=True)
+        gv.gpuvm_destroy(vm)
+    gv.free_pinned(arr)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -779,7 +825,8 @@ def main():
 
     if args.sweep:
         import oracle
-        (sweep_oversubscription if args.sweep == "oversubscription" else sweep_page_size)(gv, torch, np, inputs, oracle)
+        {"oversubscription": sweep_oversubscription, "page_size": sweep_page_size,
+         "policy": sweep_policy}[args.sweep](gv, torch, np, inputs, oracle)
         return
     link = measure_link(gv, torch, np)
     link_peak = max(link["wave_read_4k"], link["wave_read_64k"], link["wave_copy_4k"], link["hipMemcpy_h2d"])

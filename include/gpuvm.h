@@ -45,6 +45,11 @@ enum {
 enum {
     GPUVM_POLICY_FIFO  = 0, /* ring of frames + reference-counter gate (the paper's) */
     GPUVM_POLICY_CLOCK = 1, /* same ring with a second-chance reference bit          */
+    GPUVM_POLICY_CLOCK_WRITE_AWARE = 3, /* CLOCK that spares a DIRTY page one more time
+                               before evicting it, so that clean (read-mostly) pages
+                               go first and written ones are written back less often
+                               (paper: Comparisons with UVM - "delay its eviction and
+                               evict one of the least needed read-intensive pages")   */
     GPUVM_POLICY_FIFO_WAIT = 2 /* FIFO, but a leader that draws a frame in use waits
                                (bounded) for its reference counter to reach zero, as
                                the paper words it, instead of passing the frame over;
@@ -112,7 +117,7 @@ GPUVM_API int gpuvm_host_free(void *p);
  *   page_bytes        power of two, 4 KiB .. 1 MiB; every element a launcher
  *                     accesses must not straddle a page.
  *   frame_pool_bytes  HBM budget; n_frames = floor(frame_pool_bytes/page_bytes) >= 2.
- *   policy            GPUVM_POLICY_FIFO, GPUVM_POLICY_CLOCK or GPUVM_POLICY_FIFO_WAIT.
+ *   policy            GPUVM_POLICY_FIFO, _CLOCK, _CLOCK_WRITE_AWARE or _FIFO_WAIT.
  * Allocates (hipMalloc) the frame pool, page table (8 B per page), frame table
  * (4 B per frame) and counters; all pages start INVALID, all frames empty, the
  * ring cursor at 0. */

@@ -34,7 +34,8 @@
  *     bit   32     REF    CLOCK reference bit
  *     bit   33     DIRTY  frame differs from host memory
  *     bits 34..35  state  0 INVALID, 1 LOADING, 2 RESIDENT, 3 EVICTING
- *     bits 36..63  frame  valid while RESIDENT / EVICTING
+ *     bit   36     DEFER  write-aware CLOCK: the hand has spared this dirty page once
+ *     bits 37..63  frame  valid while RESIDENT / EVICTING
  * Frame table: frame_owner[f] = page whose data the frame holds (0xFFFFFFFF
  * before first use).  hand[0] is the global head cursor of the frame ring;
  * ticket t names frame t mod n_frames (paper: Eviction scheme - the leader
@@ -70,7 +71,8 @@
 #define GPUVM_PTE_DIRTY       (1ull << 33)
 #define GPUVM_PTE_STATE_SHIFT 34
 #define GPUVM_PTE_STATE_MASK  (3ull << GPUVM_PTE_STATE_SHIFT)
-#define GPUVM_PTE_FRAME_SHIFT 36
+#define GPUVM_PTE_DEFER       (1ull << 36)   /* write-aware CLOCK: dirty page already spared once */
+#define GPUVM_PTE_FRAME_SHIFT 37
 #define GPUVM_ST_INVALID  0ull
 #define GPUVM_ST_LOADING  1ull
 #define GPUVM_ST_RESIDENT 2ull
@@ -84,6 +86,10 @@ enum {
     GPUVM_S_COALESCED, GPUVM_S_WAITS, GPUVM_S_SKIPS, GPUVM_S_SWEEPS,
     GPUVM_S_PHASES, GPUVM_S_COUNT = 16
 };
+
+__device__ __forceinline__ bool gpuvm_uses_ref(unsigned int policy) {
+    return policy == GPUVM_POLICY_CLOCK || policy == GPUVM_POLICY_CLOCK_WRITE_AWARE;
+}
 
 namespace gpuvm_detail {
 
@@ -253,8 +259,16 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
                 }
                 continue;
             }
-            if (vm.policy == GPUVM_POLICY_CLOCK && (pq & GPUVM_PTE_REF)) {
+            if (gpuvm_uses_ref(vm.policy) && (pq & GPUVM_PTE_REF)) {
                 a_and(vm.pte + q, ~GPUVM_PTE_REF);            /* second chance */
+                ++sweeps;
+                continue;
+            }
+            if (vm.policy == GPUVM_POLICY_CLOCK_WRITE_AWARE && (pq & GPUVM_PTE_DIRTY) && !(pq & GPUVM_PTE_DEFER)) {
+                /* a written page costs a write-back: spare it once and look for a
+                 * clean victim first (a CAS: without a pin the page may leave) */
+                unsigned long long expect = pq;
+                a_cas(vm.pte + q, &expect, pq | GPUVM_PTE_DEFER);
                 ++sweeps;
                 continue;
             }
@@ -354,7 +368,7 @@ __device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned i
         if (w.leader) {
             unsigned long long need = 0;
             if (write && !(cur & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
-            if (vm.policy == GPUVM_POLICY_CLOCK && !(cur & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
+            if (gpuvm_uses_ref(vm.policy) && !(cur & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
             if (need) a_or(pte, need);
             if (vm.flags & GPUVM_F_ACCESS_STATS) stat_add(vm, GPUVM_S_HITS, 1);
         }
@@ -402,7 +416,7 @@ __device__ __forceinline__ bool gpuvm_peek_valid(const gpuvm_dev_t &vm, unsigned
     if (w.leader) {
         const unsigned long long again = a_load(vm.pte + page);
         same = ((again ^ token) & GPUVM_PTE_IDENT_MASK) == 0;
-        if (same && vm.policy == GPUVM_POLICY_CLOCK && !(again & GPUVM_PTE_REF)) {
+        if (same && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF)) {
             unsigned long long expect = again;                /* second-chance bit, best effort */
             a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
         }
@@ -488,7 +502,7 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
             if (resident) {
                 unsigned long long need = 0;
                 if (!(word & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
-                if (vm.policy == GPUVM_POLICY_CLOCK && !(word & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
+                if (gpuvm_uses_ref(vm.policy) && !(word & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
                 if (need) a_or(vm.pte + page, need);
             }
             a_add(vm.pte + page, ~0ull);                      /* unpin, or give the pin back */
@@ -501,7 +515,7 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
             /* second-chance bit, best effort: a CAS, because without a pin the
              * page may leave at any moment and a plain OR could then mark an
              * entry that is no longer RESIDENT */
-            if (still && vm.policy == GPUVM_POLICY_CLOCK && !(again & GPUVM_PTE_REF)) {
+            if (still && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF)) {
                 unsigned long long expect = again;
                 a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
             }

@@ -22,7 +22,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gpuvm_oracle.c")
 _LIB = os.path.join(_HERE, "libgpuvm_oracle.so")
 
-FIFO, CLOCK = 0, 1
+FIFO, CLOCK, CLOCK_WA = 0, 1, 3
 READ, WRITE, ADD = 0, 1, 2
 COUNTER_NAMES = ("faults", "hits", "evictions", "writebacks_evict",
                  "writebacks_flush", "skips", "sweeps", "phases")
@@ -74,7 +74,7 @@ def lib():
         L.sim_counters.argtypes = [vp, vp]
         L.sim_hand.argtypes = [vp]
         L.sim_hand.restype = u64
-        L.sim_state.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.sim_state.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -310,5 +310,6 @@ class PagingSim:
         dirty = np.empty(self.n_frames, np.uint8)
         pin = np.empty(self.n_frames, np.uint32)
         where = np.empty(self.n_pages, np.int64)
-        lib().sim_state(self._s, _p(owner), _p(ref), _p(dirty), _p(pin), _p(where))
-        return dict(owner=owner, ref=ref, dirty=dirty, pin=pin, where=where)
+        defer = np.empty(self.n_frames, np.uint8)
+        lib().sim_state(self._s, _p(owner), _p(ref), _p(dirty), _p(pin), _p(where), _p(defer))
+        return dict(owner=owner, ref=ref, dirty=dirty, pin=pin, where=where, defer=defer)

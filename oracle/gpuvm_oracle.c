@@ -29,6 +29,9 @@
  *       and whenever it is used, cleared when the cursor passes; FIFO is the
  *       same walk without that test;
  *     - a victim is written back only if it was written to (dirty bit);
+ *     - the write-aware CLOCK variant (the paper only names the idea: delay
+ *       the eviction of write-intensive pages) passes over a dirty page once
+ *       more after its reference bit is clear, then evicts it;
  *     - accesses arrive in phases (a group of accesses that are in flight
  *       together); each distinct page of a phase counts one hit or one fault;
  *       its faults are served in ascending page order; pins are dropped when
@@ -248,7 +251,7 @@ void oracle_scatter_increment(uint64_t *host, const uint32_t *idx, uint64_t k)
 /* Part 2: sequential paged-memory simulator                           */
 /* ------------------------------------------------------------------ */
 
-enum { SIM_FIFO = 0, SIM_CLOCK = 1 };
+enum { SIM_FIFO = 0, SIM_CLOCK = 1, SIM_CLOCK_WA = 3 };   /* 2 (wait for the drawn frame) has no sequential meaning */
 enum { SIM_READ = 0, SIM_WRITE = 1, SIM_ADD = 2 };
 enum {
     SIM_C_FAULTS = 0, SIM_C_HITS, SIM_C_EVICTIONS, SIM_C_WB_EVICT,
@@ -261,6 +264,7 @@ typedef struct sim {
     int policy;
     int64_t *owner;        /* per frame: page living there, -1 = empty     */
     uint8_t *ref, *dirty;  /* per frame                                    */
+    uint8_t *defer;        /* per frame: dirty page already spared once    */
     uint32_t *pin;         /* per frame: reference counter                 */
     int64_t *where;        /* per page: frame, -1 = not in GPU memory      */
     uint64_t *frames;      /* n_frames x page_words when host != NULL      */
@@ -272,7 +276,7 @@ typedef struct sim {
 void sim_destroy(sim_t *s)
 {
     if (!s) return;
-    free(s->owner); free(s->ref); free(s->dirty); free(s->pin);
+    free(s->owner); free(s->ref); free(s->dirty); free(s->pin); free(s->defer);
     free(s->where); free(s->frames); free(s->seen); free(s);
 }
 
@@ -288,11 +292,13 @@ sim_t *sim_create(uint64_t *host, uint64_t n_words, uint64_t page_words,
     s->owner = (int64_t *)malloc(n_frames * sizeof(int64_t));
     s->ref = (uint8_t *)calloc(n_frames, 1);
     s->dirty = (uint8_t *)calloc(n_frames, 1);
+    s->defer = (uint8_t *)calloc(n_frames, 1);
     s->pin = (uint32_t *)calloc(n_frames, sizeof(uint32_t));
     s->where = (int64_t *)malloc(s->n_pages * sizeof(int64_t));
     s->seen = (uint8_t *)calloc(s->n_pages, 1);
     s->frames = host ? (uint64_t *)calloc(n_frames * page_words, 8) : NULL;
-    if (!s->owner || !s->ref || !s->dirty || !s->pin || !s->where || !s->seen ||
+    if (policy != SIM_FIFO && policy != SIM_CLOCK && policy != SIM_CLOCK_WA) { sim_destroy(s); return NULL; }
+    if (!s->owner || !s->ref || !s->dirty || !s->defer || !s->pin || !s->where || !s->seen ||
         (host && !s->frames)) { sim_destroy(s); return NULL; }
     for (uint64_t f = 0; f < n_frames; ++f) s->owner[f] = -1;
     for (uint64_t p = 0; p < s->n_pages; ++p) s->where[p] = -1;
@@ -322,8 +328,11 @@ static void sim_fault(sim_t *s, uint64_t p)
         s->hand = (s->hand + 1) % s->n_frames;
         if (s->owner[f] < 0) break;                       /* never used yet */
         if (s->pin[f] > 0) { s->counters[SIM_C_SKIPS]++; continue; }
-        if (s->policy == SIM_CLOCK && s->ref[f]) {
+        if ((s->policy == SIM_CLOCK || s->policy == SIM_CLOCK_WA) && s->ref[f]) {
             s->ref[f] = 0; s->counters[SIM_C_SWEEPS]++; continue;
+        }
+        if (s->policy == SIM_CLOCK_WA && s->dirty[f] && !s->defer[f]) {
+            s->defer[f] = 1; s->counters[SIM_C_SWEEPS]++; continue;   /* spare a written page once */
         }
         uint64_t q = (uint64_t)s->owner[f];
         s->counters[SIM_C_EVICTIONS]++;
@@ -338,7 +347,7 @@ static void sim_fault(sim_t *s, uint64_t p)
     }
     s->owner[f] = (int64_t)p;
     s->where[p] = (int64_t)f;
-    s->dirty[f] = 0; s->ref[f] = 1; s->pin[f] = 1;
+    s->dirty[f] = 0; s->defer[f] = 0; s->ref[f] = 1; s->pin[f] = 1;
     if (s->host)
         memcpy(s->frames + f * s->page_words, s->host + p * s->page_words,
                page_len(s, p) * 8);
@@ -419,6 +428,7 @@ void sim_flush(sim_t *s)
                 memcpy(s->host + q * s->page_words, s->frames + f * s->page_words,
                        page_len(s, q) * 8);
             s->dirty[f] = 0;
+            s->defer[f] = 0;
         }
     }
 }
@@ -432,8 +442,9 @@ uint64_t sim_hand(const sim_t *s) { return s->hand; }
 
 /* owner/ref/dirty/pin per frame, where per page (any pointer may be NULL). */
 void sim_state(const sim_t *s, int64_t *owner, uint8_t *ref, uint8_t *dirty,
-               uint32_t *pin, int64_t *where)
+               uint32_t *pin, int64_t *where, uint8_t *defer)
 {
+    if (defer) memcpy(defer, s->defer, s->n_frames);
     if (owner) memcpy(owner, s->owner, s->n_frames * sizeof(int64_t));
     if (ref)   memcpy(ref, s->ref, s->n_frames);
     if (dirty) memcpy(dirty, s->dirty, s->n_frames);

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgpuvm.so")
 
 OK, EINVAL, ENOMEM, EPIN, EDEADLK, EHIP, ERANGE = 0, -1, -2, -3, -4, -5, -6
-POLICY_FIFO, POLICY_CLOCK, POLICY_FIFO_WAIT = 0, 1, 2
+POLICY_FIFO, POLICY_CLOCK, POLICY_FIFO_WAIT, POLICY_CLOCK_WRITE_AWARE = 0, 1, 2, 3
 STAT_NAMES = ("faults", "evictions", "writebacks_evict", "writebacks_flush",
               "bytes_in", "bytes_out", "hits", "wave_page_groups",
               "lanes_coalesced", "loading_waits", "alloc_skips", "alloc_sweeps",
@@ -30,7 +30,8 @@ PTE_GEN_MASK = 0xFFF00000
 PTE_REF = 1 << 32
 PTE_DIRTY = 1 << 33
 PTE_STATE_SHIFT = 34
-PTE_FRAME_SHIFT = 36
+PTE_DEFER = 1 << 36
+PTE_FRAME_SHIFT = 37
 ST_INVALID, ST_LOADING, ST_RESIDENT, ST_EVICTING = 0, 1, 2, 3
 NO_PAGE = 0xFFFFFFFF
 
@@ -323,4 +324,5 @@ def decode_pte(pte):
                 ref=((pte >> np.uint64(32)) & np.uint64(1)).astype(np.uint8),
                 dirty=((pte >> np.uint64(33)) & np.uint64(1)).astype(np.uint8),
                 state=((pte >> np.uint64(PTE_STATE_SHIFT)) & np.uint64(3)).astype(np.uint8),
+                defer=((pte >> np.uint64(36)) & np.uint64(1)).astype(np.uint8),
                 frame=(pte >> np.uint64(PTE_FRAME_SHIFT)).astype(np.int64))

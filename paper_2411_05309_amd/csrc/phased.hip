@@ -61,8 +61,13 @@ __global__ __launch_bounds__(1024) void k_phase_assign(gpuvm_dev_t vm, const uns
             if (q == GPUVM_NO_PAGE) break;
             const unsigned long long pq = vm.pte[q];
             if (pq & GPUVM_PTE_PIN_MASK) { st[GPUVM_S_SKIPS] += 1; continue; }
-            if (vm.policy == GPUVM_POLICY_CLOCK && (pq & GPUVM_PTE_REF)) {
+            if (gpuvm_uses_ref(vm.policy) && (pq & GPUVM_PTE_REF)) {
                 vm.pte[q] = pq & ~GPUVM_PTE_REF;
+                st[GPUVM_S_SWEEPS] += 1;
+                continue;
+            }
+            if (vm.policy == GPUVM_POLICY_CLOCK_WRITE_AWARE && (pq & GPUVM_PTE_DIRTY) && !(pq & GPUVM_PTE_DEFER)) {
+                vm.pte[q] = pq | GPUVM_PTE_DEFER;
                 st[GPUVM_S_SWEEPS] += 1;
                 continue;
             }

@@ -13,7 +13,7 @@ from gpu_util import Backing, check_invariants, dev, host
 
 pytestmark = pytest.mark.gpu
 
-_POL = {gv.POLICY_FIFO: oracle.FIFO, gv.POLICY_CLOCK: oracle.CLOCK}
+_POL = {gv.POLICY_FIFO: oracle.FIFO, gv.POLICY_CLOCK: oracle.CLOCK, gv.POLICY_CLOCK_WRITE_AWARE: oracle.CLOCK_WA}
 
 
 def _compare_with_replay(b, sim, frames):
@@ -31,6 +31,7 @@ def _compare_with_replay(b, sim, frames):
     assert np.array_equal(f["frame"][res], s["where"][res])
     assert np.array_equal(f["dirty"][res], s["dirty"][s["where"][res]])
     assert np.array_equal(f["ref"][res], s["ref"][s["where"][res]])
+    assert np.array_equal(f["defer"][res], s["defer"][s["where"][res]])
     return st
 
 
@@ -61,7 +62,7 @@ def test_gather_phased_equals_sequential_replay(gpu, policy, n_elems, page, fram
         assert np.array_equal(b.arr, data)
 
 
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO])
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_CLOCK_WRITE_AWARE])
 @pytest.mark.parametrize("n_elems,page,frames,n_upd,phase_len", [
     (1 << 15, 4096, 16, 20000, 12),
     ((1 << 14) + 9, 4096, 8, 6001, 5),

@@ -364,3 +364,76 @@ def test_pinned_frames_are_never_victims():
         sim.phase(np.array([1, 2], np.uint64))
         assert sorted(sim.state()["owner"].tolist()) == [1, 2]
         assert sim.counters["hits"] == 1 and sim.counters["faults"] == 3
+
+
+# ---------------------------------------------------------------- write-aware CLOCK
+
+def write_aware_queue_model(refs, writes, frames):
+    """Second chance as a queue, with one more chance for a page that was written:
+    the oldest page goes to the back with its R bit cleared if R is set; else, if
+    it is dirty and has not been spared yet, it is spared once; else it is evicted."""
+    q, st, faults, wbs = deque(), {}, 0, 0           # st[page] = [R, dirty, spared]
+    for p, w in zip(refs, writes):
+        if p in st:
+            st[p][0] = 1
+            st[p][1] |= int(w)
+            continue
+        faults += 1
+        if len(q) == frames:
+            while True:
+                old = q.popleft()
+                r, d, sp = st[old]
+                if r:
+                    st[old][0] = 0
+                    q.append(old)
+                elif d and not sp:
+                    st[old][2] = 1
+                    q.append(old)
+                else:
+                    wbs += d
+                    del st[old]
+                    break
+        q.append(p)
+        st[p] = [1, int(w), 0]
+    return faults, wbs, set(q)
+
+
+def test_write_aware_clock_equals_clock_without_writes():
+    for npages, frames, length in [(4, 2, 6), (4, 3, 7), (5, 3, 6)]:
+        for refs in itertools.product(range(npages), repeat=length):
+            a = _run_pages(list(refs), frames, CLOCK, n_pages=npages)
+            b = _run_pages(list(refs), frames, oracle.CLOCK_WA, n_pages=npages)
+            assert a.counters == b.counters and a.state()["owner"].tolist() == b.state()["owner"].tolist()
+
+
+def test_write_aware_clock_against_queue_model():
+    rng = np.random.default_rng(21)
+    for _ in range(60):
+        npages = int(rng.integers(4, 40))
+        frames = int(rng.integers(1, npages))
+        n = 2000
+        refs = np.minimum(rng.geometric(0.12, n) - 1, npages - 1).tolist()
+        writes = (rng.random(n) < 0.3).tolist()
+        f, w, resident = write_aware_queue_model(refs, writes, frames)
+        sim = _run_pages(refs, frames, oracle.CLOCK_WA, writes, n_pages=npages)
+        assert sim.counters["faults"] == f and sim.counters["writebacks_evict"] == w
+        own = sim.state()["owner"]
+        assert set(own[own >= 0].tolist()) == resident
+
+
+def test_write_aware_clock_spares_the_written_page():
+    # 2 frames: 1W 2R 3R.  The hand clears both bits, comes back to page 1 (dirty,
+    # not yet spared: spared), takes clean page 2.  Plain CLOCK evicts page 1 and
+    # pays a write-back.
+    wa = _run_pages([1, 2, 3], 2, oracle.CLOCK_WA, [True, False, False], n_pages=5)
+    ck = _run_pages([1, 2, 3], 2, CLOCK, [True, False, False], n_pages=5)
+    assert sorted(wa.state()["owner"].tolist()) == [1, 3] and wa.counters["writebacks_evict"] == 0
+    assert sorted(ck.state()["owner"].tolist()) == [2, 3] and ck.counters["writebacks_evict"] == 1
+    # spared once only: 4R finds page 1 with its chance used up
+    wa.run(np.array([4], np.uint64))
+    assert wa.counters["writebacks_evict"] == 1 and sorted(wa.state()["owner"].tolist()) == [3, 4]
+
+
+def test_waiting_policy_has_no_sequential_replay():
+    with pytest.raises(ValueError):
+        PagingSim(1, 4, 2, n_words=8)
