@@ -31,12 +31,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "filter", "vector_add", "embedding", "scatter"])
+    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "filter", "vector_add", "vector_add_overwrite", "embedding", "scatter"])
     ap.add_argument("--policy", default="clock", choices=["clock", "fifo", "fifo_wait"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
-    ap.add_argument("--sweep", default=None, choices=["oversubscription", "page_size", "policy"],
+    ap.add_argument("--sweep", default=None, choices=["oversubscription", "page_size", "policy", "writeback"],
                     help="instead of the benchmark line: one JSON line per point of a sweep")
     return ap.parse_args()
 
@@ -276,12 +276,13 @@ class VectorAddWorkload:
         self.vmb = gv.gpuvm_create(self.barr.ctypes.data, self.barr.nbytes, self.page, self.pool, policy)
         self.vmc = gv.gpuvm_create(self.carr.ctypes.data, self.carr.nbytes, self.page, self.pool, policy)
         self.useful_bytes = 12 * self.n
+        self.run = gv.gpuvm_run_vector_add
 
     def launch(self):
         gv = self.gv
         gv.gpuvm_reset(self.vmb)
         gv.gpuvm_reset(self.vmc)
-        gv.gpuvm_run_vector_add(self.vm, self.vmb, self.vmc, self.n)
+        self.run(self.vm, self.vmb, self.vmc, self.n)
         gv.gpuvm_flush(self.vmc)
         sb, sc = gv.gpuvm_stats(self.vmb), gv.gpuvm_stats(self.vmc)
         self.stats_w = {k: sb[k] + sc[k] for k in sb}
@@ -302,6 +303,16 @@ class VectorAddWorkload:
 
     def config(self):
         return {"elements": self.n}
+
+
+class VectorAddOverwriteWorkload(VectorAddWorkload):
+    """The same addition with C's pages installed without a fetch (a wavefront
+    stores whole pages of C): 16 GiB cross the link inwards instead of 24."""
+    name = "vector_add_3x8GiB_f32_64KiB_pages_2GiB_pools_then_flush_C_not_fetched"
+
+    def __init__(self, gv, torch, np, inputs, policy):
+        super().__init__(gv, torch, np, inputs, policy)
+        self.run = gv.gpuvm_run_vector_add_overwrite
 
 
 class BfsWorkload:
@@ -623,9 +634,9 @@ class ScatterWorkload:
 
 
 WORKLOADS = {"gather": GatherWorkload, "stream": StreamWorkload, "bfs": BfsWorkload, "cc": CcWorkload, "sssp": SsspWorkload,
-             "matvec_t": MatvecTWorkload, "filter": FilterWorkload, "vector_add": VectorAddWorkload,
+             "matvec_t": MatvecTWorkload, "filter": FilterWorkload, "vector_add": VectorAddWorkload, "vector_add_overwrite": VectorAddOverwriteWorkload,
              "embedding": EmbeddingWorkload, "scatter": ScatterWorkload}
-DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "matvec_t": (3, 1), "filter": (5, 1), "vector_add": (3, 1), "embedding": (2, 1), "scatter": (1, 0)}
+DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "matvec_t": (3, 1), "filter": (5, 1), "vector_add": (3, 1), "vector_add_overwrite": (3, 1), "embedding": (2, 1), "scatter": (1, 0)}
 
 
 def timed_ms(torch, fn, reps=3):
@@ -808,6 +819,50 @@ def sweep_policy(gv, torch, np, inputs, oracle):
     gv.free_pinned(arr)
 
 
+def sweep_writeback(gv, torch, np, inputs, oracle):
+    """Faults with a dirty victim, the write-back overlapped with the fetch or
+    completed before it (paper: Evaluation, Transfer-bound Applications - the
+    synchronous write-back is what its vector addition loses time to).  Uniform
+    random increments over a uint64 array much larger than the pool: nearly every
+    update faults, and every victim is dirty.  Swept over the page size and the
+    number of wavefronts in flight (tiny pools bound it by frames / 2), since the
+    overlap shortens one fault and can only pay while the link is not yet full.
+    Checked against the histogram."""
+    for page, n64, n_upd in ((4096, 1 << 25, 1 << 22), (65536, 1 << 29, 1 << 21)):
+        idx = inputs.u32_indices(300, 0, n_upd, n64)
+        d_idx = torch.from_numpy(idx.view(np.int32)).cuda()
+        arr = gv.pinned_array((n64,), np.uint64)
+        quarter = arr.nbytes // 4 // page
+        for frames, waves_per_cu, n in ((32, 8, n_upd >> 3), (64, 8, n_upd >> 2), (128, 8, n_upd >> 1), (256, 8, n_upd >> 1),
+                                        (quarter, 1, n_upd), (quarter, 4, n_upd), (quarter, 16, n_upd)):
+            ref = np.zeros(n64, np.uint64)
+            oracle.scatter_increment(ref, idx[:n])
+            for name, mode in (("serial", gv.WB_SERIAL), ("overlapped", gv.WB_OVERLAPPED)):
+                arr[...] = 0
+                vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, frames * page, gv.POLICY_CLOCK)
+                gv.gpuvm_set_writeback_mode(vm, mode)
+                gv.gpuvm_set_waves_per_cu(vm, waves_per_cu)
+                waves = gv.gpuvm_max_waves(vm)
+                e0, e1 = ev_pair(torch)
+                e0.record()
+                gv.gpuvm_run_scatter_increment(vm, d_idx, n)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                st = gv.gpuvm_stats(vm)
+                gv.gpuvm_flush(vm)
+                ok = bool(np.array_equal(arr, ref))
+                print(json.dumps({"sweep": "writeback", "workload": f"uniform_increments_u64_{n64 >> 17}MiB",
+                                  "page_bytes": page, "frames": frames, "waves": waves, "mode": name, "ms": round(ms, 2),
+                                  "faults": st["faults"], "writebacks_evict": st["writebacks_evict"],
+                                  "us_per_fault_per_wave": round(ms * 1e3 * waves / max(st["faults"], 1), 2),
+                                  "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2),
+                                  "link_out_GBps": round(st["bytes_out"] / ms / 1e6, 2), "parity": ok}), flush=True)
+                gv.gpuvm_destroy(vm)
+        gv.free_pinned(arr)
+        del d_idx
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -826,7 +881,7 @@ def main():
     if args.sweep:
         import oracle
         {"oversubscription": sweep_oversubscription, "page_size": sweep_page_size,
-         "policy": sweep_policy}[args.sweep](gv, torch, np, inputs, oracle)
+         "policy": sweep_policy, "writeback": sweep_writeback}[args.sweep](gv, torch, np, inputs, oracle)
         return
     link = measure_link(gv, torch, np)
     link_peak = max(link["wave_read_4k"], link["wave_read_64k"], link["wave_copy_4k"], link["hipMemcpy_h2d"])
@@ -866,7 +921,7 @@ def main():
     gv.gpuvm_check(W.vm)
     st = gv.gpuvm_stats(W.vm)                        # counters of the last step (reset clears them)
     if hasattr(W, "stats_w"):                        # second paged array (edge weights): add its traffic
-        for k in ("faults", "evictions", "bytes_in", "bytes_out"):
+        for k in st:
             st[k] += W.stats_w[k]
     kern_s = sum(e0.elapsed_time(e1) for e0, e1 in events) * 1e-3 / len(events)
     step_s = wall / args.steps

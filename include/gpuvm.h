@@ -72,7 +72,9 @@ typedef struct gpuvm_stats {
     uint64_t alloc_skips;       /* ring positions passed over: pinned / busy frame      */
     uint64_t alloc_sweeps;      /* CLOCK reference bits cleared by the hand             */
     uint64_t phases;            /* barrier phases run by the deterministic launchers    */
-    uint64_t reserved[3];
+    uint64_t faults_no_fetch;   /* of `faults`: pages installed for a full overwrite,
+                                   nothing read from the host                           */
+    uint64_t reserved[2];
 } gpuvm_stats_t;
 
 /* ---- device-side view: a POD copied by value into kernel arguments -----
@@ -94,6 +96,7 @@ typedef struct gpuvm_dev {
 } gpuvm_dev_t;
 
 #define GPUVM_F_ACCESS_STATS 1u   /* also count hits / groups / coalesced lanes     */
+#define GPUVM_F_OVERLAPPED_WRITEBACK 2u /* see gpuvm_set_writeback_mode              */
 #define GPUVM_STAT_SLOTS 64
 
 typedef struct gpuvm gpuvm_t;     /* opaque; owned by the library */
@@ -133,6 +136,18 @@ GPUVM_API int gpuvm_device_handle(const gpuvm_t *vm, gpuvm_dev_t *out);
  * exceeds it records GPUVM_EDEADLK and the launch returns it; 0 keeps the
  * default); access_stats != 0 turns the per-access counters on. */
 GPUVM_API int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats);
+
+/* How a fault treats a dirty victim.  GPUVM_WB_SERIAL (default): the paper's
+ * order, the write-back completes before the fetch starts.
+ * GPUVM_WB_OVERLAPPED: one pass over the frame moves the old content to the
+ * host and the new page in, the transfers of both directions in flight
+ * together - the obvious remedy for the cost of synchronous write-back that the
+ * paper's vector-addition result shows (Evaluation, "Transfer-bound
+ * Applications").  Results are the same; only the time of one fault differs,
+ * and with a whole wavefront as the mover and other wavefronts filling the
+ * link in the meantime the measured gain is a few per cent at best. */
+enum { GPUVM_WB_SERIAL = 0, GPUVM_WB_OVERLAPPED = 1 };
+GPUVM_API int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode);
 
 /* Wavefronts per compute unit the launchers aim for (1..32, default 8). */
 GPUVM_API int gpuvm_set_waves_per_cu(gpuvm_t *vm, int waves_per_cu);
@@ -189,6 +204,16 @@ GPUVM_API int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n,
  * be the same handle, C must be distinct).  C is written with gpuvm_store, its
  * pages become DIRTY and reach the host at eviction or gpuvm_flush(vm_c). */
 GPUVM_API int gpuvm_run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n,
+                                   void *stream);
+
+/* The same result with C's pages taken through gpuvm_acquire_overwrite: a
+ * wavefront owns one page of C at a time and stores all of it, so a miss on C
+ * installs a frame without reading the page from the host first - 8 of the 12
+ * bytes per element cross the link inwards instead of 12.  Not in the paper
+ * (its write faults fetch).  Same arguments and errors as above; in addition
+ * C[0..n) must end on a page boundary of C or where C ends (GPUVM_EINVAL
+ * otherwise: a page stored only in part would need its old content). */
+GPUVM_API int gpuvm_run_vector_add_overwrite(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n,
                                    void *stream);
 
 /* One pass of a streaming read-reduce over an fp32 data set: for each block of

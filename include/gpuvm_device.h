@@ -84,7 +84,7 @@ enum {
     GPUVM_S_FAULTS = 0, GPUVM_S_EVICTIONS, GPUVM_S_WB_EVICT, GPUVM_S_WB_FLUSH,
     GPUVM_S_BYTES_IN, GPUVM_S_BYTES_OUT, GPUVM_S_HITS, GPUVM_S_GROUPS,
     GPUVM_S_COALESCED, GPUVM_S_WAITS, GPUVM_S_SKIPS, GPUVM_S_SWEEPS,
-    GPUVM_S_PHASES, GPUVM_S_COUNT = 16
+    GPUVM_S_PHASES, GPUVM_S_NOFETCH, GPUVM_S_COUNT = 16
 };
 
 __device__ __forceinline__ bool gpuvm_uses_ref(unsigned int policy) {
@@ -215,6 +215,37 @@ GPUVM_DEV void wave_copy(char *dst, const char *src, unsigned int bytes, const w
         __builtin_amdgcn_raw_buffer_store_b8(__builtin_amdgcn_raw_buffer_load_b8(rs, vec_bytes + w.rank, 0, LD),
                                              rd, vec_bytes + w.rank, 0, ST);
 }
+/* Whole-wave exchange for a fault whose victim is dirty: the old content of the
+ * frame goes to `host_old` while the new page comes from `host_new`, with the
+ * loads of both directions in flight together, so the fault pays one trip over
+ * the link instead of two in a row.  Every lane reads a piece of the frame
+ * before it overwrites that same piece (the store of the new piece is issued
+ * after the store of the old one, which needs the loaded data).  Both pages
+ * are `bytes` long, a multiple of 16. */
+template <int UNROLL>
+GPUVM_DEV void swap_tier(__amdgpu_buffer_rsrc_t rf, __amdgpu_buffer_rsrc_t ro, __amdgpu_buffer_rsrc_t rn,
+                         unsigned int &o, unsigned int stride, unsigned int bytes) {
+    for (; o + (UNROLL - 1) * stride < bytes; o += UNROLL * stride) {
+        u32x4 vo[UNROLL], vn[UNROLL];
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) vn[j] = __builtin_amdgcn_raw_buffer_load_b128(rn, o + j * stride, 0, GPUVM_AUX_SYSTEM);
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) vo[j] = __builtin_amdgcn_raw_buffer_load_b128(rf, o + j * stride, 0, GPUVM_AUX_AGENT);
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) __builtin_amdgcn_raw_buffer_store_b128(vo[j], ro, o + j * stride, 0, GPUVM_AUX_SYSTEM);
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) __builtin_amdgcn_raw_buffer_store_b128(vn[j], rf, o + j * stride, 0, GPUVM_AUX_AGENT);
+    }
+}
+GPUVM_DEV void swap_frame_with_host(char *frame, char *host_old, const char *host_new, unsigned int bytes,
+                                    const wave_t &w) {
+    const __amdgpu_buffer_rsrc_t rf = make_rsrc(frame, bytes), ro = make_rsrc(host_old, bytes),
+                                 rn = make_rsrc(host_new, bytes);
+    const unsigned int stride = w.count * 16u;
+    unsigned int o = w.rank * 16u;
+    swap_tier<4>(rf, ro, rn, o, stride, bytes);       /* 8 loads in flight per lane, like wave_copy */
+    swap_tier<1>(rf, ro, rn, o, stride, bytes);
+}
 GPUVM_DEV void copy_host_to_frame(char *frame, const char *host, unsigned int bytes, const wave_t &w) {
     wave_copy<GPUVM_AUX_SYSTEM, GPUVM_AUX_AGENT>(frame, host, bytes, w);
 }
@@ -226,7 +257,7 @@ GPUVM_DEV void copy_frame_to_host(char *host, const char *frame, unsigned int by
  * wave has just moved INVALID -> LOADING.  Returns the frame, or GPUVM_NO_PAGE
  * if a bounded wait ran out (error recorded). */
 GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool write, unsigned int gen,
-                             const wave_t &w) {
+                             const wave_t &w, bool fetch = true) {
     unsigned int f = 0, victim = GPUVM_NO_PAGE, wb = 0, ok = 1;
     if (w.leader) {
         unsigned long long skips = 0, sweeps = 0;
@@ -291,20 +322,28 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
     }
     f = bcast(f); victim = bcast(victim); wb = bcast(wb);
     char *frame = vm.frames + ((size_t)f << vm.page_shift);
+    const unsigned int len = page_len(vm, page);
+    bool fetched = false;
     if (victim != GPUVM_NO_PAGE) {
         if (wb) {
-            const unsigned int len = page_len(vm, victim);
-            copy_frame_to_host(vm.host + ((size_t)victim << vm.page_shift), frame, len, w);
+            const unsigned int vlen = page_len(vm, victim);
+            if ((vm.flags & GPUVM_F_OVERLAPPED_WRITEBACK) && fetch && vlen == len && (len & 15u) == 0) {
+                /* write-back and fetch share one pass over the frame */
+                swap_frame_with_host(frame, vm.host + ((size_t)victim << vm.page_shift),
+                                     vm.host + ((size_t)page << vm.page_shift), len, w);
+                fetched = true;
+            } else {
+                copy_frame_to_host(vm.host + ((size_t)victim << vm.page_shift), frame, vlen, w);
+            }
             wait_vm();                                        /* posted before the victim can be re-read */
-            if (w.leader) { stat_add(vm, GPUVM_S_WB_EVICT, 1); stat_add(vm, GPUVM_S_BYTES_OUT, len); }
+            if (w.leader) { stat_add(vm, GPUVM_S_WB_EVICT, 1); stat_add(vm, GPUVM_S_BYTES_OUT, vlen); }
         }
         if (w.leader) {
             a_and(vm.pte + victim, GPUVM_PTE_KEEP_MASK);      /* INVALID; waiters keep their pins */
             stat_add(vm, GPUVM_S_EVICTIONS, 1);
         }
     }
-    const unsigned int len = page_len(vm, page);
-    copy_host_to_frame(frame, vm.host + ((size_t)page << vm.page_shift), len, w);
+    if (fetch && !fetched) copy_host_to_frame(frame, vm.host + ((size_t)page << vm.page_shift), len, w);
     if (w.leader) a_store(vm.frame_owner + f, page);
     wait_vm();                                                /* the page is in the frame */
     if (w.leader) {
@@ -317,20 +356,13 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
             ((unsigned long long)(gen ^ ((gen + 1u) & 0xFFFu)) << GPUVM_PTE_GEN_SHIFT);
         a_xor(vm.pte + page, flip);                           /* publish: RESIDENT */
         stat_add(vm, GPUVM_S_FAULTS, 1);
-        stat_add(vm, GPUVM_S_BYTES_IN, len);
+        if (fetch) stat_add(vm, GPUVM_S_BYTES_IN, len); else stat_add(vm, GPUVM_S_NOFETCH, 1);
     }
     return f;
 }
 
-}  // namespace gpuvm_detail
-
-/* Pin `page` (the same value in every active lane) and return the address of
- * its frame, migrating it first if it is not in GPU memory.  `write` = the
- * caller will modify the page.  Must be followed by gpuvm_release before the
- * wave acquires another page.  After a recorded error the returned pointer is
- * a valid dummy (frame 0) so that callers never dereference garbage. */
-__device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned int page_any, bool write) {
-    using namespace gpuvm_detail;
+/* lookup + pin of one page for the whole wave; see gpuvm_acquire */
+GPUVM_DEV char *acquire_page(const gpuvm_dev_t &vm, unsigned int page_any, bool write, bool fetch) {
     const wave_t w = wave_now();
     const unsigned int page = bcast(page_any);
     unsigned long long *pte = vm.pte + page;
@@ -360,7 +392,7 @@ __device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned i
     if (how == 2) return vm.frames;
     unsigned int f;
     if (how == 1) {
-        f = fault(vm, page, write, (unsigned int)(cur >> GPUVM_PTE_GEN_SHIFT) & 0xFFFu, w);
+        f = fault(vm, page, write, (unsigned int)(cur >> GPUVM_PTE_GEN_SHIFT) & 0xFFFu, w, fetch);
         if (f == GPUVM_NO_PAGE) return vm.frames;
     } else {
         cur = bcast(cur);
@@ -374,6 +406,28 @@ __device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned i
         }
     }
     return vm.frames + ((size_t)f << vm.page_shift);
+}
+
+}  // namespace gpuvm_detail
+
+/* Pin `page` (the same value in every active lane) and return the address of
+ * its frame, migrating it first if it is not in GPU memory.  `write` = the
+ * caller will modify the page.  Must be followed by gpuvm_release before the
+ * wave acquires another page of the same handle.  After a recorded error the
+ * returned pointer is a valid dummy (frame 0) so that callers never
+ * dereference garbage. */
+__device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned int page_any, bool write) {
+    return gpuvm_detail::acquire_page(vm, page_any, write, true);
+}
+
+/* The same for a caller that will store every byte of the page before it
+ * releases it: on a miss the frame is installed without reading the page from
+ * the host (its old content would be overwritten anyway), which saves one page
+ * of link traffic per fault.  The frame's bytes are undefined until written;
+ * the page is DIRTY from the start.  Not in the paper, whose write faults
+ * always fetch. */
+__device__ __forceinline__ char *gpuvm_acquire_overwrite(const gpuvm_dev_t &vm, unsigned int page_any) {
+    return gpuvm_detail::acquire_page(vm, page_any, true, false);
 }
 
 /* Drop the pin taken by gpuvm_acquire, once everything the wave issued to the
@@ -436,6 +490,14 @@ __device__ __forceinline__ gpuvm_detail::u32x2 gpuvm_frame_load_b64(const gpuvm_
 }
 __device__ __forceinline__ gpuvm_detail::u32x4 gpuvm_frame_load_b128(const gpuvm_dev_t &vm, const char *frame, unsigned int byte_off) {
     return __builtin_amdgcn_raw_buffer_load_b128(gpuvm_detail::make_rsrc(frame, 1u << vm.page_shift), byte_off, 0, GPUVM_AUX_AGENT);
+}
+/* Coherent stores to a frame held through gpuvm_acquire(.., true) or
+ * gpuvm_acquire_overwrite.  Offsets beyond the page write nothing. */
+__device__ __forceinline__ void gpuvm_frame_store_b32(const gpuvm_dev_t &vm, char *frame, unsigned int byte_off, unsigned int v) {
+    __builtin_amdgcn_raw_buffer_store_b32(v, gpuvm_detail::make_rsrc(frame, 1u << vm.page_shift), byte_off, 0, GPUVM_AUX_AGENT);
+}
+__device__ __forceinline__ void gpuvm_frame_store_b128(const gpuvm_dev_t &vm, char *frame, unsigned int byte_off, gpuvm_detail::u32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, gpuvm_detail::make_rsrc(frame, 1u << vm.page_shift), byte_off, 0, GPUVM_AUX_AGENT);
 }
 
 /* Element access with wavefront dedup: calls op(T*) once in every active lane

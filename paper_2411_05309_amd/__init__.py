@@ -18,10 +18,11 @@ LIB_PATH = os.path.join(_HERE, "libgpuvm.so")
 
 OK, EINVAL, ENOMEM, EPIN, EDEADLK, EHIP, ERANGE = 0, -1, -2, -3, -4, -5, -6
 POLICY_FIFO, POLICY_CLOCK, POLICY_FIFO_WAIT, POLICY_CLOCK_WRITE_AWARE = 0, 1, 2, 3
+WB_SERIAL, WB_OVERLAPPED = 0, 1
 STAT_NAMES = ("faults", "evictions", "writebacks_evict", "writebacks_flush",
               "bytes_in", "bytes_out", "hits", "wave_page_groups",
               "lanes_coalesced", "loading_waits", "alloc_skips", "alloc_sweeps",
-              "phases")
+              "phases", "faults_no_fetch")
 
 # page-table word layout (include/gpuvm_device.h)
 PTE_PIN_MASK = 0xFFFFF
@@ -44,7 +45,7 @@ class GpuvmError(RuntimeError):
 
 
 class Stats(C.Structure):
-    _fields_ = [(n, C.c_uint64) for n in STAT_NAMES] + [("reserved", C.c_uint64 * 3)]
+    _fields_ = [(n, C.c_uint64) for n in STAT_NAMES] + [("reserved", C.c_uint64 * 2)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n in STAT_NAMES}
@@ -68,6 +69,7 @@ _SIGNATURES = {
     "gpuvm_destroy": ([C.c_void_p], C.c_int),
     "gpuvm_device_handle": ([C.c_void_p, C.POINTER(Dev)], C.c_int),
     "gpuvm_configure": ([C.c_void_p, C.c_uint32, C.c_int], C.c_int),
+    "gpuvm_set_writeback_mode": ([C.c_void_p, C.c_int], C.c_int),
     "gpuvm_set_waves_per_cu": ([C.c_void_p, C.c_int], C.c_int),
     "gpuvm_check": ([C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_max_waves": ([C.c_void_p], C.c_int),
@@ -79,6 +81,7 @@ _SIGNATURES = {
     "gpuvm_strerror": ([C.c_int], C.c_char_p),
     "gpuvm_run_gather": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_vector_add": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
+    "gpuvm_run_vector_add_overwrite": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_stream_reduce": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_bfs": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_bfs_balanced": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
@@ -172,6 +175,10 @@ def gpuvm_configure(vm, spin_limit=0, access_stats=False):
     _call("gpuvm_configure", vm, spin_limit, int(access_stats))
 
 
+def gpuvm_set_writeback_mode(vm, mode):
+    _call("gpuvm_set_writeback_mode", vm, mode)
+
+
 def gpuvm_set_waves_per_cu(vm, waves_per_cu):
     _call("gpuvm_set_waves_per_cu", vm, waves_per_cu)
 
@@ -215,6 +222,10 @@ def gpuvm_dump_tables(vm):
 
 def gpuvm_run_gather(vm, d_idx, n, d_out, d_sum=None, stream=None):
     _call("gpuvm_run_gather", vm, _ptr(d_idx), n, _ptr(d_out), _ptr(d_sum), _stream(stream))
+
+
+def gpuvm_run_vector_add_overwrite(vm_a, vm_b, vm_c, n, stream=None):
+    _call("gpuvm_run_vector_add_overwrite", vm_a, vm_b, vm_c, n, _stream(stream))
 
 
 def gpuvm_run_vector_add(vm_a, vm_b, vm_c, n, stream=None):

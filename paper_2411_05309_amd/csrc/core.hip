@@ -166,6 +166,13 @@ int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats) {
     return GPUVM_OK;
 }
 
+int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode) {
+    if (!vm || (mode != GPUVM_WB_OVERLAPPED && mode != GPUVM_WB_SERIAL)) return GPUVM_EINVAL;
+    vm->dev.flags = mode == GPUVM_WB_OVERLAPPED ? (vm->dev.flags | GPUVM_F_OVERLAPPED_WRITEBACK)
+                                                : (vm->dev.flags & ~GPUVM_F_OVERLAPPED_WRITEBACK);
+    return GPUVM_OK;
+}
+
 int gpuvm_set_waves_per_cu(gpuvm_t *vm, int waves_per_cu) {
     if (!vm || waves_per_cu < 1 || waves_per_cu > 32) return GPUVM_EINVAL;
     vm->waves_per_cu = waves_per_cu;

@@ -103,10 +103,18 @@ __global__ __launch_bounds__(kBlock) void k_phase_migrate(gpuvm_dev_t vm, const 
     for (unsigned int j = wave; j < n; j += nwaves) {
         const phase_job job = jobs[j];
         char *frame = vm.frames + ((size_t)job.frame << vm.page_shift);
-        if (job.writeback)
-            copy_frame_to_host(vm.host + ((size_t)job.victim << vm.page_shift), frame, page_len(vm, job.victim), w);
-        if (job.writeback) wait_vm();
-        copy_host_to_frame(frame, vm.host + ((size_t)job.page << vm.page_shift), page_len(vm, job.page), w);
+        const unsigned int len = page_len(vm, job.page);
+        if (job.writeback) {
+            const unsigned int vlen = page_len(vm, job.victim);
+            if ((vm.flags & GPUVM_F_OVERLAPPED_WRITEBACK) && vlen == len && (len & 15u) == 0) {
+                swap_frame_with_host(frame, vm.host + ((size_t)job.victim << vm.page_shift),
+                                     vm.host + ((size_t)job.page << vm.page_shift), len, w);
+                continue;
+            }
+            copy_frame_to_host(vm.host + ((size_t)job.victim << vm.page_shift), frame, vlen, w);
+            wait_vm();
+        }
+        copy_host_to_frame(frame, vm.host + ((size_t)job.page << vm.page_shift), len, w);
     }
     wait_vm();
 }

@@ -49,6 +49,7 @@ __global__ __launch_bounds__(kBlock) void k_scatter_inc(gpuvm_dev_t vm, const ui
 // time (consecutive stripes to consecutive waves), so that the waves in flight
 // fault on different pages; with a plain grid-stride loop all of them would
 // stand on the same handful of pages and wait for one fetch at a time.
+template <bool OVERWRITE>
 __global__ __launch_bounds__(kBlock) void k_vector_add(gpuvm_dev_t a, gpuvm_dev_t b, gpuvm_dev_t c, size_t n) {
     const unsigned int lane = threadIdx.x & 63;
     const size_t wave = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
@@ -56,13 +57,24 @@ __global__ __launch_bounds__(kBlock) void k_vector_add(gpuvm_dev_t a, gpuvm_dev_
     const size_t stripe = (size_t)1 << (c.page_shift - 2);               // floats per page of C
     for (size_t lo = wave * stripe; lo < n; lo += nwaves * stripe) {
         const size_t hi = lo + stripe < n ? lo + stripe : n;
+        // OVERWRITE: the stripe is exactly one page of C and the wave stores all
+        // of it (the launcher admits only an n that ends on a page boundary or
+        // where C ends), so the page needs no fetch.  The pin on C's page is
+        // held across faults on A and B, which draw on pools of their own.
+        const unsigned int page_c = (unsigned int)(lo >> (c.page_shift - 2));
+        char *fc = OVERWRITE ? gpuvm_acquire_overwrite(c, page_c) : nullptr;
         for (size_t i0 = lo; i0 < hi; i0 += 64) {
             const size_t i = i0 + lane;
             const bool want = i < hi;
             const float x = gpuvm_load_if<float>(a, want ? i : 0, want);
             const float y = gpuvm_load_if<float>(b, want ? i : 0, want);
-            gpuvm_store_if<float>(c, want ? i : 0, x + y, want);
+            if (OVERWRITE) {
+                if (want) gpuvm_frame_store_b32(c, fc, (unsigned int)(i - lo) * 4u, __float_as_uint(x + y));
+            } else {
+                gpuvm_store_if<float>(c, want ? i : 0, x + y, want);
+            }
         }
+        if (OVERWRITE) gpuvm_release(c, page_c);
     }
 }
 
@@ -293,16 +305,30 @@ int gpuvm_run_scatter_increment(gpuvm_t *vm, const uint32_t *d_idx, size_t n, vo
     return GPUVM_OK;
 }
 
-int gpuvm_run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n, void *stream) {
+static int run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n, bool overwrite, void *stream) {
     if (!vm_a || !vm_b || !vm_c || vm_a == vm_c || vm_b == vm_c) return GPUVM_EINVAL;
     if (n * 4 > vm_a->dev.bytes || n * 4 > vm_b->dev.bytes || n * 4 > vm_c->dev.bytes) return GPUVM_ERANGE;
+    // without a fetch the last page touched must be stored completely: n ends
+    // on a page boundary of C or where C itself ends
+    if (overwrite && (n * 4) % vm_c->page_bytes != 0 && n * 4 != vm_c->dev.bytes) return GPUVM_EINVAL;
     if (n == 0) return GPUVM_OK;
     const size_t work = (n * 4 + vm_c->page_bytes - 1) / vm_c->page_bytes;       // page-sized stripes
     const int waves = std::min({launch_waves(vm_a, work), launch_waves(vm_b, work), launch_waves(vm_c, work)});
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
-    k_vector_add<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, vm_c->dev, n);
+    if (overwrite)
+        k_vector_add<true><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, vm_c->dev, n);
+    else
+        k_vector_add<false><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, vm_c->dev, n);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
+}
+
+int gpuvm_run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n, void *stream) {
+    return run_vector_add(vm_a, vm_b, vm_c, n, false, stream);
+}
+
+int gpuvm_run_vector_add_overwrite(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n, void *stream) {
+    return run_vector_add(vm_a, vm_b, vm_c, n, true, stream);
 }
 
 int gpuvm_run_stream_reduce(gpuvm_t *vm, size_t block_elems, double *d_sums, void *stream) {

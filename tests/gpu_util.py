@@ -66,10 +66,12 @@ def check_invariants(b, read_only=True, pristine=None):
     assert st["faults"] - st["evictions"] == len(res)
     assert st["writebacks_evict"] <= st["evictions"]
     last_len = b.arr.nbytes - (b.n_pages - 1) * b.page_bytes
+    fetched = st["faults"] - st["faults_no_fetch"]          # pages installed for a full overwrite are not read
+    assert fetched >= 0
     if last_len == b.page_bytes:
-        assert st["bytes_in"] == st["faults"] * b.page_bytes
+        assert st["bytes_in"] == fetched * b.page_bytes
     else:
-        assert st["faults"] * b.page_bytes - (b.page_bytes - last_len) * st["faults"] <= st["bytes_in"] <= st["faults"] * b.page_bytes
+        assert fetched * b.page_bytes - (b.page_bytes - last_len) * fetched <= st["bytes_in"] <= fetched * b.page_bytes
     if read_only:
         assert st["writebacks_evict"] == 0 and st["writebacks_flush"] == 0 and st["bytes_out"] == 0
         assert not np.any(f["dirty"])

@@ -62,18 +62,20 @@ def test_gather_phased_equals_sequential_replay(gpu, policy, n_elems, page, fram
         assert np.array_equal(b.arr, data)
 
 
+@pytest.mark.parametrize("wb_mode", [gv.WB_OVERLAPPED, gv.WB_SERIAL])
 @pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_CLOCK_WRITE_AWARE])
 @pytest.mark.parametrize("n_elems,page,frames,n_upd,phase_len", [
     (1 << 15, 4096, 16, 20000, 12),
     ((1 << 14) + 9, 4096, 8, 6001, 5),
 ])
-def test_scatter_phased_equals_sequential_replay(gpu, policy, n_elems, page, frames, n_upd, phase_len):
+def test_scatter_phased_equals_sequential_replay(gpu, policy, n_elems, page, frames, n_upd, phase_len, wb_mode):
     r = inputs.zipf_ranks(6, 0, n_upd, n_elems, 0.9) - 1
     idx = ((r * 40503) % n_elems).astype(np.uint32)
     want = np.zeros(n_elems, np.uint64)
     sim = oracle.PagingSim(page // 8, frames, _POL[policy], host=want)
     sim.run(idx.astype(np.uint64), op=oracle.ADD, val=1, phase_len=phase_len)
     with Backing(np.zeros(n_elems, np.uint64), page, frames * page, policy) as b:
+        gv.gpuvm_set_writeback_mode(b.vm, wb_mode)
         gv.gpuvm_run_scatter_increment_phased(b.vm, dev(idx), n_upd, phase_len)
         st = _compare_with_replay(b, sim, frames)
         assert st["writebacks_evict"] > 0

@@ -127,13 +127,15 @@ def test_embedding_bag(gpu, dim, rows, page, frames, bags, bag_len):
 
 # ---------------------------------------------------------------- scatter-increment
 
+@pytest.mark.parametrize("wb_mode", [gv.WB_OVERLAPPED, gv.WB_SERIAL])
 @pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT, gv.POLICY_CLOCK_WRITE_AWARE])
 @pytest.mark.parametrize("n_elems,page,frames,n_upd", [
     (1 << 17, 4096, 32, 200000),            # 256 pages over 32 frames: dirty evictions
     ((1 << 15) + 77, 4096, 16, 50001),      # short last page
     (1 << 14, 65536, 8, 30000),             # fits: only the flush writes back
+    (1 << 17, 65536, 8, 20000),             # 64 KiB pages, dirty evictions
 ])
-def test_scatter_increment(gpu, policy, n_elems, page, frames, n_upd):
+def test_scatter_increment(gpu, policy, n_elems, page, frames, n_upd, wb_mode):
     idx = inputs.scatter_indices(3, 0, n_upd, n_elems)
     # spread the hot head so that evictions really are dirty and re-faulted
     idx = ((idx.astype(np.uint64) * 40503) % n_elems).astype(np.uint32)
@@ -141,6 +143,7 @@ def test_scatter_increment(gpu, policy, n_elems, page, frames, n_upd):
     want = np.zeros(n_elems, np.uint64)
     oracle.scatter_increment(want, idx)
     with Backing(np.zeros(n_elems, np.uint64), page, frames * page, policy) as b:
+        gv.gpuvm_set_writeback_mode(b.vm, wb_mode)
         d_idx = dev(idx)
         half = n_upd // 2
         gv.gpuvm_run_scatter_increment(b.vm, d_idx, half)
@@ -293,3 +296,38 @@ def test_vector_add_through_three_paged_vectors(gpu, n, page, frames):
         assert np.array_equal(bc.arr, oracle.vector_add(a, a))
         with pytest.raises(gv.GpuvmError):
             gv.gpuvm_run_vector_add(ba.vm, bb.vm, ba.vm, n)
+
+
+@pytest.mark.parametrize("n,page,frames", [(1 << 20, 65536, 16), ((1 << 18) + 777, 4096, 16), (5000, 4096, 8)])
+def test_vector_add_overwrite_installs_without_fetching(gpu, n, page, frames):
+    a = inputs.f32_uniform(1, 0, n)
+    b = inputs.f32_uniform(2, 0, n)
+    want = oracle.vector_add(a, b)
+    with Backing(a, page, frames * page) as ba, Backing(b, page, frames * page) as bb, \
+            Backing(np.full(n, -9.0, np.float32), page, frames * page) as bc:
+        gv.gpuvm_run_vector_add_overwrite(ba.vm, bb.vm, bc.vm, n)
+        for x in (ba, bb, bc):
+            gv.gpuvm_check(x.vm)
+        check_invariants(ba, read_only=True, pristine=a)
+        check_invariants(bb, read_only=True, pristine=b)
+        stc, *_ = check_invariants(bc, read_only=False)
+        assert stc["faults"] == bc.n_pages and stc["faults_no_fetch"] == bc.n_pages and stc["bytes_in"] == 0
+        gv.gpuvm_flush(bc.vm)
+        assert np.array_equal(bc.arr, want)                              # bit-exact fp32
+        # second run over the pages still resident (hits) and the evicted ones (misses again)
+        gv.gpuvm_run_vector_add_overwrite(ba.vm, ba.vm, bc.vm, n)
+        gv.gpuvm_flush(bc.vm)
+        assert np.array_equal(bc.arr, oracle.vector_add(a, a))
+        assert gv.gpuvm_stats(bc.vm)["bytes_in"] == 0
+        # a prefix that ends on a page boundary leaves the rest of C alone ...
+        part = (n * 4 // page // 2) * (page // 4)
+        if part:
+            gv.gpuvm_run_vector_add_overwrite(ba.vm, bb.vm, bc.vm, part)
+            gv.gpuvm_flush(bc.vm)
+            assert np.array_equal(bc.arr[:part], want[:part])
+            assert np.array_equal(bc.arr[part:], oracle.vector_add(a, a)[part:])
+        # ... and one that ends inside a page is refused (the page would need its old content)
+        with pytest.raises(gv.GpuvmError):
+            gv.gpuvm_run_vector_add_overwrite(ba.vm, bb.vm, bc.vm, n - 3 if (n - 3) * 4 % page else n - 5)
+        with pytest.raises(gv.GpuvmError):
+            gv.gpuvm_run_vector_add_overwrite(ba.vm, bb.vm, ba.vm, n)
