@@ -191,7 +191,12 @@ GPUVM_API const char *gpuvm_strerror(int code);
  * unpin (paper: System Overview steps 1-7; Paged Memory System Design) -
  * inside its kernel.  All array arguments are device pointers.  Launches are
  * asynchronous on `stream` unless stated; a kernel-side GPUVM_EDEADLK is
- * reported by the next synchronising call on the handle. */
+ * reported by the next synchronising call on the handle.
+ * Launches on one handle must be ordered one after the other (same stream, or
+ * events): each is sized so that its wavefronts can hold at most half of the
+ * frames at once, which is what guarantees progress; two launches running
+ * together on one handle may exceed that, and then the bounded waits end them
+ * with GPUVM_EDEADLK instead of hanging.  Different handles are independent. */
 
 /* Random gather over a uint32 data set: out[k] = data[idx[k]], *sum += sum_k out[k]
  * (d_sum: one uint64 in device memory, accumulated with atomics; may be NULL).

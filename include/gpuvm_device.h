@@ -500,103 +500,44 @@ __device__ __forceinline__ void gpuvm_frame_store_b128(const gpuvm_dev_t &vm, ch
     __builtin_amdgcn_raw_buffer_store_b128(v, gpuvm_detail::make_rsrc(frame, 1u << vm.page_shift), byte_off, 0, GPUVM_AUX_AGENT);
 }
 
-/* Element access with wavefront dedup: calls op(T*) once in every active lane
- * whose `want` is true, on the lane's element, grouping lanes by page.  Lanes
- * with want == false take no element but help to move pages; calling this
- * with all lanes of the wave active (and `want` as the predicate) is what
- * keeps a fault one link round trip wide - under divergence only the active
- * lanes can copy.
- *
- * Hit pass (all groups at once): the lanes are grouped by page with ALU work
- * only, then
- *   - reads are optimistic: the leader loads the page's word, the lanes read
- *     their elements from the frame it names, and the leader loads the word
- *     again; if state, frame and install generation are unchanged the frame
- *     held the page all the while (eviction changes the word before the frame
- *     is reused, re-installation bumps the generation) and the values stand.
- *     No atomic, no reference count: readers of a hot page do not serialise on
- *     its word and never block its eviction;
- *   - writes pin: every group leader takes a reference with one fetch_add, all
- *     in the same instruction; resident groups update their elements, wait,
- *     mark the page DIRTY and unpin.  No wave waits while it holds these pins.
- * Miss pass: groups whose page was not resident (or whose optimistic read did
- * not validate) go through gpuvm_acquire one page at a time, so that a wave
- * never holds more than one frame while it waits or allocates. */
-template <typename T, typename Op>
-__device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write, bool want,
-                                             Op op) {
-    using namespace gpuvm_detail;
-    const unsigned long long byte = elem * sizeof(T);
-    const unsigned int page = (unsigned int)(byte >> vm.page_shift);              /* address split */
-    const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
-    const unsigned int lane = __lane_id();
+namespace gpuvm_detail {
 
-    /* group the wanting lanes by page: leader_lane = lowest lane with my page */
-    unsigned int leader_lane = lane;
+/* for the counters only: number of distinct pages among the wanting lanes */
+GPUVM_DEV unsigned int count_page_groups(unsigned int page, bool want) {
     unsigned int n_groups = 0;
-    {
-        bool ungrouped = want;
-        for (;;) {
-            const unsigned long long todo = __builtin_amdgcn_ballot_w64(ungrouped);
-            if (todo == 0) break;
-            const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
-            const unsigned int group_page = __builtin_amdgcn_readlane(page, first);
-            if (ungrouped && page == group_page) { leader_lane = first; ungrouped = false; }
-            ++n_groups;
-        }
+    bool ungrouped = want;
+    for (;;) {
+        const unsigned long long todo = __builtin_amdgcn_ballot_w64(ungrouped);
+        if (todo == 0) break;
+        const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
+        if (page == (unsigned int)__builtin_amdgcn_readlane(page, first)) ungrouped = false;
+        ++n_groups;
     }
-    const bool is_leader = want && leader_lane == lane;
+    return n_groups;
+}
 
-    /* hit pass */
-    unsigned long long word = 0;
-    if (is_leader) word = write ? a_add(vm.pte + page, 1ull) : a_load(vm.pte + page);
-    {
-        const unsigned int lo = __shfl((unsigned int)word, (int)leader_lane, 64);
-        const unsigned int hi = __shfl((unsigned int)(word >> 32), (int)leader_lane, 64);
-        word = ((unsigned long long)hi << 32) | lo;
+/* second half of an optimistic read: `word` is what the lane read from the
+ * page's entry before it read the frame, the frame reads have returned; true
+ * if the entry still names the same installation of the page.  Sets the
+ * second-chance bit if the hand has cleared it (best effort: a CAS, because
+ * without a pin the page may leave at any moment and a plain OR could then
+ * mark an entry that is no longer RESIDENT). */
+GPUVM_DEV bool optimistic_read_stands(const gpuvm_dev_t &vm, unsigned int page, unsigned long long word,
+                                      unsigned long long again) {
+    const bool still = ((again ^ word) & GPUVM_PTE_IDENT_MASK) == 0;
+    if (still && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF)) {
+        unsigned long long expect = again;
+        a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
     }
-    bool resident = want && ((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
-    if (resident)
-        op(reinterpret_cast<T *>(vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off));
-    wait_vm();
-    if (write) {
-        if (is_leader) {
-            if (resident) {
-                unsigned long long need = 0;
-                if (!(word & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
-                if (gpuvm_uses_ref(vm.policy) && !(word & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
-                if (need) a_or(vm.pte + page, need);
-            }
-            a_add(vm.pte + page, ~0ull);                      /* unpin, or give the pin back */
-        }
-    } else {
-        unsigned int still = 0;
-        if (is_leader && resident) {
-            const unsigned long long again = a_load(vm.pte + page);
-            still = ((again ^ word) & GPUVM_PTE_IDENT_MASK) == 0;
-            /* second-chance bit, best effort: a CAS, because without a pin the
-             * page may leave at any moment and a plain OR could then mark an
-             * entry that is no longer RESIDENT */
-            if (still && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF)) {
-                unsigned long long expect = again;
-                a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
-            }
-        }
-        still = __shfl(still, (int)leader_lane, 64);
-        resident = resident && still != 0;                    /* else: redo through the pinned path */
-    }
-    if (vm.flags & GPUVM_F_ACCESS_STATS) {
-        const unsigned long long wanting = __builtin_amdgcn_ballot_w64(want);
-        const unsigned long long hit_groups = __builtin_amdgcn_ballot_w64(is_leader && resident);
-        if (wave_now().leader) {
-            stat_add(vm, GPUVM_S_GROUPS, n_groups);
-            stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(wanting) - n_groups);
-            stat_add(vm, GPUVM_S_HITS, (unsigned long long)__popcll(hit_groups));
-        }
-    }
+    return still;
+}
 
-    /* miss pass: one page at a time */
-    bool pending = want && !resident;
+/* miss pass: the lanes in `pending` go through gpuvm_acquire one page at a
+ * time (all active lanes help to move each page), so that the wave never holds
+ * more than one frame while it waits or allocates */
+template <typename T, typename Op>
+GPUVM_DEV void access_missing(const gpuvm_dev_t &vm, unsigned int page, unsigned int off, bool write, bool pending,
+                              Op op) {
     for (;;) {
         const unsigned long long todo = __builtin_amdgcn_ballot_w64(pending);
         if (todo == 0) break;
@@ -609,6 +550,104 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
         }
         gpuvm_release(vm, group_page);
     }
+}
+
+}  // namespace gpuvm_detail
+
+/* Element access with wavefront dedup: calls op(T*) once in every active lane
+ * whose `want` is true, on the lane's element.  Lanes with want == false take
+ * no element but help to move pages; calling this with all lanes of the wave
+ * active (and `want` as the predicate) is what keeps a fault one link round
+ * trip wide - under divergence only the active lanes can copy.
+ *
+ * Hit pass (all lanes at once):
+ *   - reads are optimistic and need no grouping: every lane loads its page's
+ *     word (lanes on one page load one address, which the memory pipeline
+ *     merges), reads its element from the frame the word names and loads the
+ *     word again; if state, frame and install generation are unchanged the
+ *     frame held the page all the while (eviction changes the word before the
+ *     frame is reused, re-installation bumps the generation) and the value
+ *     stands.  No atomic, no reference count: readers of a hot page do not
+ *     serialise on its word and never block its eviction;
+ *   - writes pin: the lanes are grouped by page with ALU work only (lowest lane
+ *     of a page = its leader), every leader takes a reference with one
+ *     fetch_add, all in the same instruction; resident groups update their
+ *     elements, wait, mark the page DIRTY and unpin.  No wave waits while it
+ *     holds these pins.
+ * Miss pass: lanes whose page was not resident (or whose optimistic read did
+ * not validate) are grouped by page - one leader, one fault per page and wave -
+ * and go through gpuvm_acquire one page at a time, so that a wave never holds
+ * more than one frame while it waits or allocates. */
+template <typename T, typename Op>
+__device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write, bool want,
+                                             Op op) {
+    using namespace gpuvm_detail;
+    const unsigned long long byte = elem * sizeof(T);
+    const unsigned int page = (unsigned int)(byte >> vm.page_shift);              /* address split */
+    const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
+    const unsigned int lane = __lane_id();
+    bool resident;
+    unsigned int n_groups = 0;
+
+    if (!write) {
+        /* hit pass, reads: every lane on its own - the loads of lanes that share
+         * a page fall on one address and are merged by the memory pipeline, so
+         * no grouping is needed */
+        const unsigned long long word = want ? a_load(vm.pte + page) : 0ull;
+        resident = want && ((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
+        if (resident)
+            op(reinterpret_cast<T *>(vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off));
+        wait_vm();
+        if (resident) resident = optimistic_read_stands(vm, page, word, a_load(vm.pte + page));
+    } else {
+        /* hit pass, writes: group the wanting lanes by page (leader_lane = lowest
+         * lane with my page) so that a page takes one reference per wave */
+        unsigned int leader_lane = lane;
+        {
+            bool ungrouped = want;
+            for (;;) {
+                const unsigned long long todo = __builtin_amdgcn_ballot_w64(ungrouped);
+                if (todo == 0) break;
+                const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
+                const unsigned int group_page = __builtin_amdgcn_readlane(page, first);
+                if (ungrouped && page == group_page) { leader_lane = first; ungrouped = false; }
+                ++n_groups;
+            }
+        }
+        const bool is_leader = want && leader_lane == lane;
+        unsigned long long word = 0;
+        if (is_leader) word = a_add(vm.pte + page, 1ull);
+        {
+            const unsigned int lo = __shfl((unsigned int)word, (int)leader_lane, 64);
+            const unsigned int hi = __shfl((unsigned int)(word >> 32), (int)leader_lane, 64);
+            word = ((unsigned long long)hi << 32) | lo;
+        }
+        resident = want && ((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
+        if (resident)
+            op(reinterpret_cast<T *>(vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off));
+        wait_vm();
+        if (is_leader) {
+            if (resident) {
+                unsigned long long need = 0;
+                if (!(word & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
+                if (gpuvm_uses_ref(vm.policy) && !(word & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
+                if (need) a_or(vm.pte + page, need);
+            }
+            a_add(vm.pte + page, ~0ull);                      /* unpin, or give the pin back */
+        }
+    }
+    if (vm.flags & GPUVM_F_ACCESS_STATS) {
+        /* pages, not lanes: a page with any lane still missing counts as a miss */
+        if (!write) n_groups = count_page_groups(page, want);
+        const unsigned int n_missing = count_page_groups(page, want && !resident);
+        const unsigned long long wanting = __builtin_amdgcn_ballot_w64(want);
+        if (wave_now().leader) {
+            stat_add(vm, GPUVM_S_GROUPS, n_groups);
+            stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(wanting) - n_groups);
+            stat_add(vm, GPUVM_S_HITS, n_groups - n_missing);
+        }
+    }
+    access_missing<T>(vm, page, off, write, want && !resident, op);
 }
 
 /* Elements are 4 or 8 bytes wide and are read, written and updated with
