@@ -447,36 +447,47 @@ __device__ __forceinline__ void gpuvm_release(const gpuvm_dev_t &vm, unsigned in
  * the page during all of those reads (state, frame and install generation are
  * unchanged), false means the values must be thrown away and the page taken
  * with gpuvm_acquire.  Nothing is pinned, so readers of a hot page do not
- * serialise on its word and never hold up an eviction. */
+ * serialise on its word and never hold up an eviction.
+ *
+ * The same in four steps, for callers that keep several such reads in flight
+ * (all the words, then all the frame reads, one wait, all the re-checks):
+ *   token = gpuvm_peek_begin(vm, page);  frame = gpuvm_token_frame(vm, token);
+ *   ... gpuvm_frame_load_*(vm, frame, ..) if frame != nullptr ...
+ *   gpuvm_wait_reads();  again = gpuvm_peek_begin(vm, page);
+ *   ok = gpuvm_peek_same(vm, page, token, again);
+ * Every lane loads the word itself (one address, one request), so there is no
+ * leader and no broadcast between the steps. */
+__device__ __forceinline__ unsigned long long gpuvm_peek_begin(const gpuvm_dev_t &vm, unsigned int page) {
+    return gpuvm_detail::a_load(vm.pte + page);
+}
+__device__ __forceinline__ const char *gpuvm_token_frame(const gpuvm_dev_t &vm, unsigned long long token) {
+    if (((token & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT) return nullptr;
+    return vm.frames + ((size_t)(token >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift);
+}
+__device__ __forceinline__ void gpuvm_wait_reads() { gpuvm_detail::wait_vm(); }
+__device__ __forceinline__ bool gpuvm_peek_same(const gpuvm_dev_t &vm, unsigned int page, unsigned long long token,
+                                                unsigned long long again) {
+    using namespace gpuvm_detail;
+    const bool same = ((again ^ token) & GPUVM_PTE_IDENT_MASK) == 0 &&
+                      ((token & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
+    if (same && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF) && wave_now().leader) {
+        unsigned long long expect = again;                    /* second-chance bit, best effort */
+        a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
+    }
+    if (same && (vm.flags & GPUVM_F_ACCESS_STATS) && wave_now().leader) stat_add(vm, GPUVM_S_HITS, 1);
+    return same;
+}
 __device__ __forceinline__ const char *gpuvm_peek(const gpuvm_dev_t &vm, unsigned int page_any,
                                                   unsigned long long *token) {
-    using namespace gpuvm_detail;
-    const wave_t w = wave_now();
-    const unsigned int page = bcast(page_any);
-    unsigned long long word = 0;
-    if (w.leader) word = a_load(vm.pte + page);
-    word = bcast(word);
-    *token = word;
-    if (((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT) return nullptr;
-    return vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift);
+    const unsigned int page = gpuvm_detail::bcast(page_any);
+    *token = gpuvm_peek_begin(vm, page);
+    return gpuvm_token_frame(vm, *token);
 }
 __device__ __forceinline__ bool gpuvm_peek_valid(const gpuvm_dev_t &vm, unsigned int page_any,
                                                  unsigned long long token) {
-    using namespace gpuvm_detail;
-    const wave_t w = wave_now();
-    const unsigned int page = bcast(page_any);
-    wait_vm();                                                /* the reads have returned */
-    unsigned int same = 0;
-    if (w.leader) {
-        const unsigned long long again = a_load(vm.pte + page);
-        same = ((again ^ token) & GPUVM_PTE_IDENT_MASK) == 0;
-        if (same && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF)) {
-            unsigned long long expect = again;                /* second-chance bit, best effort */
-            a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
-        }
-        if (same && (vm.flags & GPUVM_F_ACCESS_STATS)) stat_add(vm, GPUVM_S_HITS, 1);
-    }
-    return bcast(same) != 0;
+    const unsigned int page = gpuvm_detail::bcast(page_any);
+    gpuvm_wait_reads();                                       /* the reads have returned */
+    return gpuvm_peek_same(vm, page, token, gpuvm_peek_begin(vm, page));
 }
 
 /* Coherent reads of frame memory for wave-level users of gpuvm_acquire:

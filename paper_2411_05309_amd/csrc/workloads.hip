@@ -123,49 +123,67 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
     const size_t wave = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
     const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
     const unsigned int row_bytes = 64u * VPL * 4u;
+    constexpr int kRowBatch = 4;
+    auto load_row = [&](const char *p, unsigned int o) {
+        vec_t r4;
+        if constexpr (VPL == 1) {
+            r4 = __uint_as_float(gpuvm_frame_load_b32(vm, p, o));
+        } else if constexpr (VPL == 2) {
+            const u32x2 r = gpuvm_frame_load_b64(vm, p, o);
+            r4.x = __uint_as_float(r.x); r4.y = __uint_as_float(r.y);
+        } else {
+            const u32x4 r = gpuvm_frame_load_b128(vm, p, o);
+            r4.x = __uint_as_float(r.x); r4.y = __uint_as_float(r.y);
+            r4.z = __uint_as_float(r.z); r4.w = __uint_as_float(r.w);
+        }
+        return r4;
+    };
     for (size_t bag = wave; bag < bags; bag += nwaves) {
         vec_t acc = 0.0f;
         for (unsigned int j0 = 0; j0 < bag_len; j0 += 64) {
             const unsigned int nj = min(64u, bag_len - j0);
             int my_id = 0;
             if (lane < nj) my_id = ids[bag * bag_len + j0 + lane];
-            for (unsigned int j = 0; j < nj; ++j) {
-                const unsigned long long id = (unsigned int)__builtin_amdgcn_readlane(my_id, j);
-                if (id >= n_rows) { if (lane == 0) raise_error(vm, GPUVM_ERANGE); continue; }
-                const unsigned long long byte = id * row_bytes;
-                const unsigned int page = (unsigned int)(byte >> vm.page_shift);
-                const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
-                const unsigned int o = off + lane * (VPL * 4u);
-                auto load_row = [&](const char *p) {
-                    vec_t r4;
-                    if constexpr (VPL == 1) {
-                        r4 = __uint_as_float(gpuvm_frame_load_b32(vm, p, o));
-                    } else if constexpr (VPL == 2) {
-                        const u32x2 r = gpuvm_frame_load_b64(vm, p, o);
-                        r4.x = __uint_as_float(r.x); r4.y = __uint_as_float(r.y);
-                    } else {
-                        const u32x4 r = gpuvm_frame_load_b128(vm, p, o);
-                        r4.x = __uint_as_float(r.x); r4.y = __uint_as_float(r.y);
-                        r4.z = __uint_as_float(r.z); r4.w = __uint_as_float(r.w);
+            // kRowBatch rows at a time: their table words, their row reads and
+            // their re-checks are in flight together; hot rows are read without
+            // a reference, a miss (or a page that left meanwhile) goes through
+            // the pinned path; the rows are added in listed order either way
+            for (unsigned int j0b = 0; j0b < nj; j0b += kRowBatch) {
+                unsigned int page[kRowBatch], o[kRowBatch];
+                unsigned long long token[kRowBatch], again[kRowBatch];
+                const char *p[kRowBatch];
+                vec_t v[kRowBatch];
+                bool live[kRowBatch];
+#pragma unroll
+                for (int b = 0; b < kRowBatch; ++b) {
+                    const unsigned int j = j0b + b;
+                    const unsigned long long id = (unsigned int)__builtin_amdgcn_readlane(my_id, j < nj ? j : 0);
+                    live[b] = j < nj && id < n_rows;
+                    if (j < nj && id >= n_rows && lane == 0) raise_error(vm, GPUVM_ERANGE);
+                    const unsigned long long byte = (live[b] ? id : 0ull) * row_bytes;
+                    page[b] = (unsigned int)(byte >> vm.page_shift);
+                    o[b] = (unsigned int)(byte & ((1ull << vm.page_shift) - 1)) + lane * (VPL * 4u);
+                    token[b] = gpuvm_peek_begin(vm, page[b]);
+                }
+#pragma unroll
+                for (int b = 0; b < kRowBatch; ++b) {
+                    p[b] = live[b] ? gpuvm_token_frame(vm, token[b]) : nullptr;
+                    v[b] = 0.0f;
+                    if (p[b]) v[b] = load_row(p[b], o[b]);
+                }
+                gpuvm_wait_reads();
+#pragma unroll
+                for (int b = 0; b < kRowBatch; ++b) again[b] = gpuvm_peek_begin(vm, page[b]);
+#pragma unroll
+                for (int b = 0; b < kRowBatch; ++b) {
+                    if (!live[b]) continue;
+                    if (!(p[b] && gpuvm_peek_same(vm, page[b], token[b], again[b]))) {
+                        const char *q = gpuvm_acquire(vm, page[b], false);
+                        v[b] = load_row(q, o[b]);
+                        gpuvm_release(vm, page[b]);
                     }
-                    return r4;
-                };
-                // hot rows are read without a reference; a miss (or a page that
-                // left meanwhile) goes through the pinned path
-                vec_t v;
-                unsigned long long token;
-                const char *p = gpuvm_peek(vm, page, &token);
-                bool ok = false;
-                if (p) {
-                    v = load_row(p);
-                    ok = gpuvm_peek_valid(vm, page, token);
+                    acc += v[b];
                 }
-                if (!ok) {
-                    p = gpuvm_acquire(vm, page, false);
-                    v = load_row(p);
-                    gpuvm_release(vm, page);
-                }
-                acc += v;
             }
         }
         *reinterpret_cast<vec_t *>(out + bag * (64u * VPL) + lane * VPL) = acc;
