@@ -221,6 +221,14 @@ GPUVM_API int gpuvm_run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, 
 GPUVM_API int gpuvm_run_vector_add_overwrite(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n,
                                    void *stream);
 
+/* Fault-ahead of pages [first_page, first_page + n_pages): every page of the
+ * range that is not resident is migrated (evicting as usual), nothing is read
+ * from it.  The counterpart of the prefetch hints the paper applies to its UVM
+ * baseline (Evaluation), for callers that know what the next kernel will
+ * touch; a range larger than the pool only turns the pool over.
+ * GPUVM_ERANGE if the range leaves the data set. */
+GPUVM_API int gpuvm_run_prefetch(gpuvm_t *vm, size_t first_page, size_t n_pages, void *stream);
+
 /* One pass of a streaming read-reduce over an fp32 data set: for each block of
  * block_elems consecutive floats (a multiple of the page's float count),
  * d_sums[b] = sum in fp64.  One wavefront per page, consecutive pages to

@@ -440,6 +440,14 @@ __device__ __forceinline__ void gpuvm_release(const gpuvm_dev_t &vm, unsigned in
     if (w.leader) a_add(vm.pte + page, ~0ull);                /* pin - 1 */
 }
 
+/* Fault-ahead: make `page` resident (if it is not) and let go of it at once;
+ * the data is not touched.  For waves that run ahead of the ones that will
+ * use the page, the device-side counterpart of a prefetch hint. */
+__device__ __forceinline__ void gpuvm_touch(const gpuvm_dev_t &vm, unsigned int page_any) {
+    (void)gpuvm_acquire(vm, page_any, false);
+    gpuvm_release(vm, page_any);
+}
+
 /* Optimistic page-level read for wave-level users (same page in every lane):
  * gpuvm_peek returns the frame of `page` if it is RESIDENT right now, without
  * taking a reference, and the page's word in *token; read the frame with
@@ -532,11 +540,12 @@ GPUVM_DEV unsigned int count_page_groups(unsigned int page, bool want) {
  * if the entry still names the same installation of the page.  Sets the
  * second-chance bit if the hand has cleared it (best effort: a CAS, because
  * without a pin the page may leave at any moment and a plain OR could then
- * mark an entry that is no longer RESIDENT). */
+ * mark an entry that is no longer RESIDENT); `may_mark` names the one lane
+ * that does so when the whole wave reads one page. */
 GPUVM_DEV bool optimistic_read_stands(const gpuvm_dev_t &vm, unsigned int page, unsigned long long word,
-                                      unsigned long long again) {
+                                      unsigned long long again, bool may_mark) {
     const bool still = ((again ^ word) & GPUVM_PTE_IDENT_MASK) == 0;
-    if (still && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF)) {
+    if (still && may_mark && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF)) {
         unsigned long long expect = again;
         a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
     }
@@ -601,15 +610,35 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
     unsigned int n_groups = 0;
 
     if (!write) {
-        /* hit pass, reads: every lane on its own - the loads of lanes that share
-         * a page fall on one address and are merged by the memory pipeline, so
-         * no grouping is needed */
-        const unsigned long long word = want ? a_load(vm.pte + page) : 0ull;
+        /* hit pass, reads.  One page for the whole wave (unit stride, a row
+         * segment): its first wanting lane loads the word for everybody.  Several
+         * pages: every lane on its own - the loads of lanes that share a page
+         * fall on one address, so no grouping is needed. */
+        const unsigned long long wanting = __builtin_amdgcn_ballot_w64(want);
+        const unsigned int first = wanting ? (unsigned int)__ffsll((long long)wanting) - 1u : 0u;
+        const bool one_page =
+            __builtin_amdgcn_ballot_w64(want && page != (unsigned int)__builtin_amdgcn_readlane(page, first)) == 0;
+        auto load_word = [&]() {
+            unsigned long long w = 0;
+            if (one_page) {
+                if (want && lane == first) w = a_load(vm.pte + page);
+                const unsigned int lo = __builtin_amdgcn_readlane((unsigned int)w, first);
+                const unsigned int hi = __builtin_amdgcn_readlane((unsigned int)(w >> 32), first);
+                w = ((unsigned long long)hi << 32) | lo;
+            } else if (want) {
+                w = a_load(vm.pte + page);
+            }
+            return w;
+        };
+        const unsigned long long word = load_word();
         resident = want && ((word & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
         if (resident)
             op(reinterpret_cast<T *>(vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off));
         wait_vm();
-        if (resident) resident = optimistic_read_stands(vm, page, word, a_load(vm.pte + page));
+        if (__builtin_amdgcn_ballot_w64(resident)) {
+            const unsigned long long again = load_word();
+            if (resident) resident = optimistic_read_stands(vm, page, word, again, !one_page || lane == first);
+        }
     } else {
         /* hit pass, writes: group the wanting lanes by page (leader_lane = lowest
          * lane with my page) so that a page takes one reference per wave */
@@ -702,5 +731,27 @@ template <typename T>
 __device__ __forceinline__ void gpuvm_atomic_add(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
     gpuvm_atomic_add_if<T>(vm, elem, v, true);
 }
+
+/* Array-like view for kernels written in the style of the paper's listing
+ * (System Overview: an array-like structure, so that c[i] = a[i] + b[i] needs
+ * no other change): v[i] reads, v[i] = x stores, v[i] += x adds atomically.
+ * at(i, want) is the same with the lane's predicate, for code that keeps the
+ * whole wave on the access so that all lanes help to move pages. */
+template <typename T>
+struct gpuvm_array {
+    gpuvm_dev_t vm;
+    struct ref {
+        const gpuvm_dev_t &vm;
+        unsigned long long i;
+        bool want;
+        __device__ __forceinline__ operator T() const { return gpuvm_load_if<T>(vm, i, want); }
+        __device__ __forceinline__ const ref &operator=(T v) const { gpuvm_store_if<T>(vm, i, v, want); return *this; }
+        __device__ __forceinline__ const ref &operator=(const ref &o) const { return *this = (T)o; }
+        __device__ __forceinline__ const ref &operator+=(T v) const { gpuvm_atomic_add_if<T>(vm, i, v, want); return *this; }
+    };
+    __device__ __forceinline__ ref operator[](unsigned long long i) const { return ref{vm, i, true}; }
+    __device__ __forceinline__ ref at(unsigned long long i, bool want) const { return ref{vm, want ? i : 0ull, want}; }
+    __device__ __forceinline__ unsigned long long size() const { return vm.bytes / sizeof(T); }
+};
 
 #endif /* GPUVM_DEVICE_H */

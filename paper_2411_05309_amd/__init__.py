@@ -80,6 +80,7 @@ _SIGNATURES = {
     "gpuvm_dump_tables": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_strerror": ([C.c_int], C.c_char_p),
     "gpuvm_run_gather": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_run_prefetch": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_vector_add": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_vector_add_overwrite": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_stream_reduce": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
@@ -222,6 +223,10 @@ def gpuvm_dump_tables(vm):
 
 def gpuvm_run_gather(vm, d_idx, n, d_out, d_sum=None, stream=None):
     _call("gpuvm_run_gather", vm, _ptr(d_idx), n, _ptr(d_out), _ptr(d_sum), _stream(stream))
+
+
+def gpuvm_run_prefetch(vm, first_page, n_pages, stream=None):
+    _call("gpuvm_run_prefetch", vm, first_page, n_pages, _stream(stream))
 
 
 def gpuvm_run_vector_add_overwrite(vm_a, vm_b, vm_c, n, stream=None):

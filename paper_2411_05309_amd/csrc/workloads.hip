@@ -60,6 +60,7 @@ __global__ __launch_bounds__(kBlock) void k_vector_add(gpuvm_dev_t a, gpuvm_dev_
     const size_t wave = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
     const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
     const size_t stripe = (size_t)1 << (c.page_shift - 2);               // floats per page of C
+    const gpuvm_array<float> A{a}, B{b}, C{c};
     for (size_t lo = wave * stripe; lo < n; lo += nwaves * stripe) {
         const size_t hi = lo + stripe < n ? lo + stripe : n;
         // OVERWRITE: the stripe is exactly one page of C and the wave stores all
@@ -71,16 +72,22 @@ __global__ __launch_bounds__(kBlock) void k_vector_add(gpuvm_dev_t a, gpuvm_dev_
         for (size_t i0 = lo; i0 < hi; i0 += 64) {
             const size_t i = i0 + lane;
             const bool want = i < hi;
-            const float x = gpuvm_load_if<float>(a, want ? i : 0, want);
-            const float y = gpuvm_load_if<float>(b, want ? i : 0, want);
             if (OVERWRITE) {
+                const float x = A.at(i, want), y = B.at(i, want);
                 if (want) gpuvm_frame_store_b32(c, fc, (unsigned int)(i - lo) * 4u, __float_as_uint(x + y));
             } else {
-                gpuvm_store_if<float>(c, want ? i : 0, x + y, want);
+                C.at(i, want) = (float)A.at(i, want) + (float)B.at(i, want);     // the listing's c[i] = a[i] + b[i]
             }
         }
         if (OVERWRITE) gpuvm_release(c, page_c);
     }
+}
+
+// Fault-ahead of a page range: wave w touches pages first + w, first + w + nwaves, ...
+__global__ __launch_bounds__(kBlock) void k_prefetch(gpuvm_dev_t vm, unsigned int first, unsigned int count) {
+    const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const unsigned int nwaves = (gridDim.x * kBlock) >> 6;
+    for (unsigned int j = wave; j < count; j += nwaves) gpuvm_touch(vm, first + j);
 }
 
 // Streaming read-reduce: wave w takes pages w, w + nwaves, ...; the page's
@@ -235,8 +242,7 @@ __global__ __launch_bounds__(kBlock) void k_matvec_t(gpuvm_dev_t vm, unsigned lo
                 __builtin_amdgcn_s_sleep(32);
             }
             if (row + skew < at) continue;                    // every compute wave is already past it
-            gpuvm_acquire(vm, page, false);
-            gpuvm_release(vm, page);
+            gpuvm_touch(vm, page);
         }
         return;
     }
@@ -352,6 +358,18 @@ int gpuvm_run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n, 
 
 int gpuvm_run_vector_add_overwrite(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n, void *stream) {
     return run_vector_add(vm_a, vm_b, vm_c, n, true, stream);
+}
+
+int gpuvm_run_prefetch(gpuvm_t *vm, size_t first_page, size_t n_pages, void *stream) {
+    if (!vm) return GPUVM_EINVAL;
+    if (first_page > vm->dev.n_pages || n_pages > vm->dev.n_pages - first_page) return GPUVM_ERANGE;
+    if (n_pages == 0) return GPUVM_OK;
+    const int waves = launch_waves(vm, n_pages);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    k_prefetch<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, (unsigned int)first_page,
+                                                                           (unsigned int)n_pages);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
 }
 
 int gpuvm_run_stream_reduce(gpuvm_t *vm, size_t block_elems, double *d_sums, void *stream) {

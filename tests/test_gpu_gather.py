@@ -153,3 +153,34 @@ def test_bounded_waits_drain_and_report(gpu):
         got, _ = run_gather(b, idx)
         assert np.array_equal(got, want)
         check_invariants(b, read_only=True, pristine=data)
+
+
+def test_prefetch_makes_a_range_resident(gpu):
+    n_elems, page, frames = 1 << 18, 4096, 64
+    data = inputs.u32_values(5, 0, n_elems)
+    with Backing(data, page, frames * page) as b:
+        gv.gpuvm_run_prefetch(b.vm, 100, 40)
+        gv.gpuvm_check(b.vm)
+        st, f, *_ = check_invariants(b, read_only=True, pristine=data)
+        assert st["faults"] == 40 and st["evictions"] == 0
+        assert np.all(f["state"][100:140] == gv.ST_RESIDENT)
+        assert np.count_nonzero(f["state"] == gv.ST_RESIDENT) == 40
+        # a gather inside the range finds everything in place
+        idx = (100 * 1024 + inputs.u32_indices(6, 0, 5000, 1 << 20) % (40 * 1024)).astype(np.uint32)
+        want, want_sum = oracle.gather(data, idx)
+        got, got_sum = run_gather(b, idx)
+        assert np.array_equal(got, want) and got_sum == want_sum
+        assert gv.gpuvm_stats(b.vm)["faults"] == 40
+        # prefetching it again moves nothing; a range beyond the pool turns the pool over
+        gv.gpuvm_run_prefetch(b.vm, 100, 40)
+        gv.gpuvm_check(b.vm)
+        assert gv.gpuvm_stats(b.vm)["faults"] == 40
+        gv.gpuvm_run_prefetch(b.vm, 0, b.n_pages)
+        gv.gpuvm_check(b.vm)
+        st, f, *_ = check_invariants(b, read_only=True, pristine=data)
+        assert np.count_nonzero(f["state"] == gv.ST_RESIDENT) == frames
+        gv.gpuvm_run_prefetch(b.vm, b.n_pages, 0)                       # empty range at the end: fine
+        for first, count in ((b.n_pages, 1), (0, b.n_pages + 1), (b.n_pages + 1, 0)):
+            with pytest.raises(gv.GpuvmError) as e:
+                gv.gpuvm_run_prefetch(b.vm, first, count)
+            assert e.value.code == gv.ERANGE
