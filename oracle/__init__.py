@@ -62,6 +62,7 @@ def lib():
             f.argtypes = [vp, u64, vp, u64, u64, vp]
         L.oracle_scatter_increment.argtypes = [vp, vp, u64]
         L.oracle_matvec_t.argtypes = [vp, u64, u64, vp, vp, vp]
+        L.oracle_matvec.argtypes = [vp, u64, u64, vp, vp, vp]
         L.oracle_filter_sum.argtypes = [vp, vp, u64, C.c_uint32, vp, vp]
         L.sim_create.argtypes = [vp, u64, u64, u64, C.c_int]
         L.sim_create.restype = vp
@@ -205,6 +206,17 @@ def scatter_increment(host, idx):
     assert idx.size == 0 or int(idx.max()) < host.size
     lib().oracle_scatter_increment(_p(host), _p(idx), idx.size)
     return host
+
+
+def matvec(A, x):
+    """y = A x in double precision (columns ascending) and sum_j |A[i][j] x[j]| per row."""
+    A = _arr(A, np.float32)
+    x = _arr(x, np.float32)
+    assert A.ndim == 2 and x.shape == (A.shape[1],)
+    y = np.empty(A.shape[0], np.float64)
+    yabs = np.empty(A.shape[0], np.float64)
+    lib().oracle_matvec(_p(A), A.shape[0], A.shape[1], _p(x), _p(y), _p(yabs))
+    return y, yabs
 
 
 def matvec_t(A, x):

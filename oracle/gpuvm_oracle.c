@@ -213,6 +213,25 @@ void oracle_embedding_bag_abs(const float *table, uint64_t dim, const int32_t *i
         }
 }
 
+/* Matrix-vector product: y[i] = sum_j A[i][j] * x[j], row-major A, double
+ * precision, j ascending (the row-per-thread kernel of the paper's
+ * transfer-bound applications: MVT's first product, ATAX's first step);
+ * yabs[i] = sum_j |A[i][j] * x[j]| (tolerance scale). */
+void oracle_matvec(const float *A, uint64_t rows, uint64_t cols, const float *x,
+                   double *y, double *yabs)
+{
+    for (uint64_t i = 0; i < rows; ++i) {
+        double acc = 0.0, aabs = 0.0;
+        for (uint64_t j = 0; j < cols; ++j) {
+            double t = (double)A[i * cols + j] * (double)x[j];
+            acc += t;
+            aabs += t < 0 ? -t : t;
+        }
+        y[i] = acc;
+        if (yabs) yabs[i] = aabs;
+    }
+}
+
 /* Transposed matrix-vector product: y[j] = sum_i A[i][j] * x[i], row-major A,
  * double precision; yabs[j] = sum_i |A[i][j] * x[i]| (tolerance scale). */
 void oracle_matvec_t(const float *A, uint64_t rows, uint64_t cols, const float *x,

@@ -258,6 +258,27 @@ def test_matvec_t_against_numpy_and_closed_form():
     assert yt.shape == (300,)
 
 
+def test_matvec_against_numpy_closed_form_and_its_transpose():
+    A = np.arange(12, dtype=np.float32).reshape(4, 3)            # rows 0 1 2 / 3 4 5 / 6 7 8 / 9 10 11
+    x = np.array([1, 10, 100], np.float32)
+    y, yabs = oracle.matvec(A, x)
+    assert y.tolist() == [210.0, 543.0, 876.0, 1209.0] and yabs.tolist() == y.tolist()
+    A = inputs.f32_uniform(3, 0, 300 * 70).reshape(300, 70)
+    x = inputs.f32_uniform(4, 0, 70)
+    y, yabs = oracle.matvec(A, x)
+    ref = A.astype(np.float64) @ x.astype(np.float64)
+    assert np.max(np.abs(y - ref)) <= 1e-12
+    assert np.all(yabs >= np.abs(y)) and np.allclose(yabs, np.abs(A.astype(np.float64) * x[None, :]).sum(1), rtol=1e-12)
+    # A x is (A^T)^T x: the two products pin each other through an explicit transpose
+    yt, _ = oracle.matvec_t(np.ascontiguousarray(A.T), x)
+    assert np.max(np.abs(y - yt)) <= 1e-12
+    # a sign pattern that a dropped or transposed term would break: row i of the identity picks x[i]
+    assert oracle.matvec(np.eye(5, dtype=np.float32), np.arange(5, dtype=np.float32))[0].tolist() == [0, 1, 2, 3, 4]
+    # terms that cancel: the scale keeps what the sum loses
+    y, yabs = oracle.matvec(np.array([[1, -1]], np.float32), np.array([3, 3], np.float32))
+    assert y.tolist() == [0.0] and yabs.tolist() == [6.0]
+
+
 def test_filter_sum_against_numpy():
     key = inputs.u32_values(5, 0, 100000)
     val = inputs.u32_values(6, 0, 100000)
