@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "filter", "vector_add", "vector_add_overwrite", "embedding", "scatter"])
+    ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "matvec", "filter", "vector_add", "vector_add_overwrite", "embedding", "scatter"])
     ap.add_argument("--policy", default="clock", choices=["clock", "fifo", "fifo_wait"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -469,6 +469,36 @@ class MatvecTWorkload:
         return {"rows": self.rows, "cols": self.cols}
 
 
+class MatvecWorkload(MatvecTWorkload):
+    """y = A x over the same matrix, one thread per row: the 64 lanes of a
+    wavefront stand on 64 different pages and walk along their rows."""
+    kernel = "k_matvec_rows"
+    name = "matvec_32768x32768_f32_row_per_thread_64KiB_pages_1GiB_pool"
+
+    def __init__(self, gv, torch, np, inputs, policy):
+        super().__init__(gv, torch, np, inputs, policy)
+        self.x = inputs.f32_uniform(4, 0, self.cols)
+        self.d_x = torch.from_numpy(self.x).cuda()
+        self.d_y = torch.zeros(self.rows, dtype=torch.float64, device="cuda")
+
+    def launch(self):
+        self.gv.gpuvm_run_matvec(self.vm, self.rows, self.cols, self.d_x, self.d_y)
+
+    def verify(self, oracle):
+        np = self.np
+        got = self.d_y.cpu().numpy()
+        ok = True
+        for r in np.linspace(0, self.rows - 64, 16).astype(np.int64):     # sampled row blocks
+            want, scale = oracle.matvec(self.arr[r:r + 64], self.x)
+            ok &= bool(np.all(np.abs(got[r:r + 64] - want) <= 1e-5 * scale))
+        return ok
+
+    def cpu_baseline(self, oracle):
+        t0 = time.perf_counter()
+        oracle.matvec(self.arr[:1024], self.x)
+        return (time.perf_counter() - t0) * (self.rows / 1024), "1024 of the 32768 rows, scaled"
+
+
 class FilterWorkload:
     """Filter-then-gather over two uint32 columns of 2^28 rows (1 GiB each), 4 KiB
     pages, 256 MiB pool per column, selectivity 0.08 %."""
@@ -680,9 +710,9 @@ class ScatterWorkload:
 
 
 WORKLOADS = {"gather": GatherWorkload, "stream": StreamWorkload, "bfs": BfsWorkload, "cc": CcWorkload, "sssp": SsspWorkload,
-             "matvec_t": MatvecTWorkload, "filter": FilterWorkload, "vector_add": VectorAddWorkload, "vector_add_overwrite": VectorAddOverwriteWorkload,
+             "matvec_t": MatvecTWorkload, "matvec": MatvecWorkload, "filter": FilterWorkload, "vector_add": VectorAddWorkload, "vector_add_overwrite": VectorAddOverwriteWorkload,
              "embedding": EmbeddingWorkload, "scatter": ScatterWorkload}
-DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "matvec_t": (3, 1), "filter": (5, 1), "vector_add": (3, 1), "vector_add_overwrite": (3, 1), "embedding": (2, 1), "scatter": (1, 0)}
+DEFAULT_STEPS = {"gather": (20, 3), "stream": (5, 1), "bfs": (3, 1), "cc": (2, 0), "sssp": (2, 0), "matvec_t": (3, 1), "matvec": (3, 1), "filter": (5, 1), "vector_add": (3, 1), "vector_add_overwrite": (3, 1), "embedding": (2, 1), "scatter": (1, 0)}
 
 
 def timed_ms(torch, fn, reps=3):

@@ -288,6 +288,15 @@ GPUVM_API int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_
 GPUVM_API int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x,
                                  double *d_y, void *stream);
 
+/* y = A x over the same kind of matrix, one thread per ROW (the first product
+ * of the paper's MVT, the first step of its ATAX): the lanes of a wavefront
+ * stand on 64 different pages and walk along their rows.  cols must be a
+ * multiple of 4 and rows * cols * 4 = bytes (GPUVM_EINVAL otherwise); d_x[cols]
+ * fp32, d_y[rows] fp64 out (fp64 accumulation, columns ascending).  The
+ * launcher keeps the rows in flight within 3/4 of the pool. */
+GPUVM_API int gpuvm_run_matvec(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x,
+                               double *d_y, void *stream);
+
 /* Filter-then-gather over two paged uint32 columns of equal length (paper:
  * Query Evaluation Benchmarks - scan one column, fetch another only for the
  * rows that pass): *d_count = #{i : key[i] > threshold}, *d_sum = sum of

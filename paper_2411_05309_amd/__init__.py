@@ -90,6 +90,7 @@ _SIGNATURES = {
     "gpuvm_run_sssp_balanced": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_embedding_bag": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_matvec_t": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_run_matvec": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_filter_sum": ([C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_scatter_increment": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_gather_phased": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
@@ -268,6 +269,10 @@ def gpuvm_run_sssp_balanced(vm, vm_weights, d_row_ptr, nv, src, d_dist, stream=N
 
 def gpuvm_run_embedding_bag(vm, dim, d_ids, bags, bag_len, d_out, stream=None):
     _call("gpuvm_run_embedding_bag", vm, dim, _ptr(d_ids), bags, bag_len, _ptr(d_out), _stream(stream))
+
+
+def gpuvm_run_matvec(vm, rows, cols, d_x, d_y, stream=None):
+    _call("gpuvm_run_matvec", vm, rows, cols, _ptr(d_x), _ptr(d_y), _stream(stream))
 
 
 def gpuvm_run_matvec_t(vm, rows, cols, d_x, d_y, stream=None):

@@ -245,6 +245,29 @@ def test_matvec_t_column_order(gpu, rows, cols, page, frames):
             gv.gpuvm_run_matvec_t(b.vm, rows + 1, cols, dev(x), d_y)
 
 
+@pytest.mark.parametrize("rows,cols,page,frames", [
+    (512, 4096, 4096, 512),           # a row = 4 pages; 2048 pages over 512 frames, the rows in flight fit
+    (300, 1000, 4096, 16),            # ragged rows, short last page, far more rows in flight than frames
+    (200, 16384, 65536, 64),          # a row = one 64 KiB page
+])
+def test_matvec_row_per_thread(gpu, rows, cols, page, frames):
+    A = inputs.f32_uniform(3, 0, rows * cols).reshape(rows, cols)
+    x = inputs.f32_uniform(4, 0, cols)
+    want, scale = oracle.matvec(A, x)
+    with Backing(A, page, frames * page) as b:
+        d_y = torch.full((rows,), -1.0, dtype=torch.float64, device="cuda")
+        gv.gpuvm_run_matvec(b.vm, rows, cols, dev(x), d_y)
+        gv.gpuvm_check(b.vm)
+        got = d_y.cpu().numpy()
+        assert np.all(np.abs(got - want) <= 1e-5 * scale)          # stated bar
+        assert np.array_equal(got, want)                             # same order, fp64, no contraction: exact
+        st, *_ = check_invariants(b, read_only=True, pristine=A)
+        assert st["faults"] >= b.n_pages
+        for bad_rows, bad_cols in ((rows + 1, cols), (rows * 2, cols // 2 + 1)):
+            with pytest.raises(gv.GpuvmError):
+                gv.gpuvm_run_matvec(b.vm, bad_rows, bad_cols, dev(x), d_y)
+
+
 @pytest.mark.parametrize("n,page,frames,sel", [
     (1 << 20, 4096, 32, 0.0008),      # the paper's 0.08 % selectivity, 4 KiB pages
     ((1 << 18) + 333, 4096, 16, 0.02),
