@@ -788,6 +788,36 @@ def sweep_oversubscription(gv, torch, np, inputs, oracle):
                               "faults": st["faults"], "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "parity": ok}), flush=True)
             gv.gpuvm_destroy(vm)
     gv.free_pinned(carr)
+    # the two matrix-vector products of the paper's transfer-bound applications
+    # (access along columns: the case in which its UVM baseline degrades worst)
+    n, page = 16384, 65536
+    marr = gv.pinned_array((n, n), np.float32)
+    torch.from_numpy(marr).view(-1).copy_(inputs.t_f32_uniform(3, 0, n * n, "cuda"))
+    torch.cuda.synchronize()
+    x = inputs.f32_uniform(4, 0, n)
+    d_x = torch.from_numpy(x).cuda()
+    d_y = torch.zeros(n, dtype=torch.float64, device="cuda")
+    for name, run_fn, ref_fn in (("matvec_t_16384x16384_column_order_64KiB_pages", gv.gpuvm_run_matvec_t, oracle.matvec_t),
+                                 ("matvec_16384x16384_row_per_thread_64KiB_pages", gv.gpuvm_run_matvec, oracle.matvec)):
+        want, scale = ref_fn(marr, x)
+        base = None
+        for lv in levels:
+            pool = int(marr.nbytes / (lv + 1)) // page * page
+            vm = gv.gpuvm_create(marr.ctypes.data, marr.nbytes, page, pool, gv.POLICY_CLOCK)
+
+            def run():
+                gv.gpuvm_reset(vm)
+                run_fn(vm, n, n, d_x, d_y)
+            ms = timed_ms(torch, run)
+            gv.gpuvm_check(vm)
+            st = gv.gpuvm_stats(vm)
+            ok = bool(np.all(np.abs(d_y.cpu().numpy() - want) <= 1e-5 * scale))
+            base = base or ms
+            print(json.dumps({"sweep": "oversubscription", "workload": name, "policy": "clock",
+                              "level": lv, "pool_bytes": pool, "ms": round(ms, 3), "slowdown_vs_level0": round(ms / base, 3),
+                              "faults": st["faults"], "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "parity": ok}), flush=True)
+            gv.gpuvm_destroy(vm)
+    gv.free_pinned(marr)
 
 
 def sweep_page_size(gv, torch, np, inputs, oracle):

@@ -276,32 +276,36 @@ __global__ __launch_bounds__(kBlock) void k_matvec_t(gpuvm_dev_t vm, unsigned lo
 // Matrix-vector product y = A x over a paged row-major fp32 matrix, a thread
 // per ROW (the first product of the paper's MVT / the first step of its ATAX):
 // the 64 lanes of a wave stand on 64 different rows, i.e. on 64 different
-// pages, and each walks along its own row, four floats (16 bytes) per access.
+// pages, and each walks along its own row, 64 (or 16) bytes per access.
 // A page is used by one lane only, for page_bytes / 16 consecutive steps, and
 // all lanes reach their next page at the same step.  Reads go through the
 // element accessor: 64 optimistic hits per step, and at a page boundary 64
 // faults per wave, one after the other.  The launcher keeps the rows in flight
 // (one page each) below the pool size; beyond that every step would fault.
 // fp64 accumulation, columns ascending.
-struct f32x4_t { float v[4]; };
+template <int FLOATS> struct f32_chunk_t { float v[FLOATS]; };
+template <int FLOATS>     // floats per access: 16 (64 bytes in flight per lane and step) or 4
 __global__ __launch_bounds__(kBlock) void k_matvec_rows(gpuvm_dev_t vm, unsigned long long rows, unsigned long long cols,
                                                          const float *__restrict__ x, double *__restrict__ y) {
+    typedef f32_chunk_t<FLOATS> chunk_t;
     const size_t nthreads = (size_t)gridDim.x * kBlock;
     const unsigned long long rows_up = (rows + 63) & ~63ull;      // whole waves iterate together
     for (unsigned long long r = (size_t)blockIdx.x * kBlock + threadIdx.x; r < rows_up; r += nthreads) {
         const bool want = r < rows;
         double acc = 0.0;
-        for (unsigned long long j = 0; j < cols; j += 4) {
-            unsigned long long lo = 0, hi = 0;
-            gpuvm_access<f32x4_t>(vm, want ? (r * cols + j) >> 2 : 0, false, want, [&](f32x4_t *p) {
+        for (unsigned long long j = 0; j < cols; j += FLOATS) {
+            unsigned long long w[FLOATS / 2] = {};
+            gpuvm_access<chunk_t>(vm, want ? (r * cols + j) / FLOATS : 0, false, want, [&](chunk_t *p) {
                 unsigned long long *q = reinterpret_cast<unsigned long long *>(p);
-                lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int k = 0; k < FLOATS / 2; ++k)
+                    w[k] = __hip_atomic_load(q + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             });
-            acc += (double)__uint_as_float((unsigned int)lo) * (double)x[j];
-            acc += (double)__uint_as_float((unsigned int)(lo >> 32)) * (double)x[j + 1];
-            acc += (double)__uint_as_float((unsigned int)hi) * (double)x[j + 2];
-            acc += (double)__uint_as_float((unsigned int)(hi >> 32)) * (double)x[j + 3];
+#pragma unroll
+            for (int k = 0; k < FLOATS / 2; ++k) {
+                acc += (double)__uint_as_float((unsigned int)w[k]) * (double)x[j + 2 * k];
+                acc += (double)__uint_as_float((unsigned int)(w[k] >> 32)) * (double)x[j + 2 * k + 1];
+            }
         }
         if (want) y[r] = acc;
     }
@@ -472,7 +476,10 @@ int gpuvm_run_matvec(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, do
     const int fit = (int)std::min<size_t>(vm->dev.n_frames * 3 / 4 / 64, 1 << 20) / kWavesPerBlock * kWavesPerBlock;
     const int waves = std::min(launch_waves(vm, (rows + 63) / 64), std::max(fit, kWavesPerBlock));
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
-    k_matvec_rows<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, d_x, d_y);
+    if (cols % 16 == 0)
+        k_matvec_rows<16><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, d_x, d_y);
+    else
+        k_matvec_rows<4><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, d_x, d_y);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }
