@@ -877,6 +877,33 @@ def sweep_page_size(gv, torch, np, inputs, oracle):
                           "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "waves": gv.gpuvm_max_waves(vm), "parity": ok}), flush=True)
         gv.gpuvm_destroy(vm)
     gv.free_pinned(garr)
+    # edge-balanced BFS (R-MAT scale 24, 1 GiB of col_idx, pool 256 MiB): the paper
+    # runs its graph workloads on 8 KiB pages against UVM's 64 KiB
+    scale = 24
+    d_rp, d_ci = inputs.t_rmat_csr(3, scale, "cuda")
+    carr = gv.pinned_array((d_ci.numel(),), np.int32)
+    torch.from_numpy(carr).copy_(d_ci)
+    del d_ci
+    torch.cuda.synchronize()
+    nv = 1 << scale
+    want = oracle.bfs(d_rp.cpu().numpy(), carr, 0)
+    d_level = torch.zeros(nv, dtype=torch.int32, device="cuda")
+    for shift in range(12, 21):
+        page = 1 << shift
+        vm = gv.gpuvm_create(carr.ctypes.data, carr.nbytes, page, 256 << 20, gv.POLICY_CLOCK)
+
+        def run():
+            gv.gpuvm_reset(vm)
+            gv.gpuvm_run_bfs_balanced(vm, d_rp, nv, 0, d_level)
+        ms = timed_ms(torch, run)
+        st = gv.gpuvm_stats(vm)
+        ok = bool(np.array_equal(d_level.cpu().numpy(), want))
+        print(json.dumps({"sweep": "page_size", "workload": "bfs_balanced_rmat24_pool_256MiB", "page_bytes": page,
+                          "ms": round(ms, 3), "faults": st["faults"], "faults_per_s": round(st["faults"] / ms * 1e3),
+                          "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "link_in_GB": round(st["bytes_in"] / 1e9, 3),
+                          "waves": gv.gpuvm_max_waves(vm), "parity": ok}), flush=True)
+        gv.gpuvm_destroy(vm)
+    gv.free_pinned(carr)
 
 
 def sweep_policy(gv, torch, np, inputs, oracle):
