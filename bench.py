@@ -1023,7 +1023,12 @@ def main():
         args.steps = DEFAULT_STEPS[args.workload][0]
     if args.warmup is None:
         args.warmup = DEFAULT_STEPS[args.workload][1]
+    def say(what):                                   # progress of a long run, on stderr
+        print(f"[bench {time.strftime('%H:%M:%S')}] {what}", file=sys.stderr, flush=True)
+
+    say(f"host link measured; building the inputs of '{args.workload}'")
     W = WORKLOADS[args.workload](gv, torch, np, inputs, policy)
+    say("inputs ready")
     if args.workload == "bfs" and args.bfs_naive:
         W.naive, W.kernel = True, "k_bfs_level"
         W.name += "_vertex_chunks"
@@ -1045,6 +1050,7 @@ def main():
         step()
     gv.gpuvm_check(W.vm)
     torch.cuda.synchronize()
+    say(f"{args.warmup} warm-up step(s) done")
     events = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -1059,8 +1065,10 @@ def main():
     kern_s = sum(e0.elapsed_time(e1) for e0, e1 in events) * 1e-3 / len(events)
     step_s = wall / args.steps
 
+    say(f"{args.steps} timed step(s) done, checking against the oracle")
     import oracle
     parity = W.verify(oracle)
+    say("checked")
 
     out = {
         "metric": "effective GB/s (host-link bytes serviced by GPU-thread page faults) at 4x oversubscription",
