@@ -975,7 +975,7 @@ def sweep_writeback(gv, torch, np, inputs, oracle):
                 vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, frames * page, gv.POLICY_CLOCK)
                 gv.gpuvm_set_writeback_mode(vm, mode)
                 gv.gpuvm_set_waves_per_cu(vm, waves_per_cu)
-                waves = gv.gpuvm_max_waves(vm)
+                waves = gv.gpuvm_max_waves_duplex(vm)
                 e0, e1 = ev_pair(torch)
                 e0.record()
                 gv.gpuvm_run_scatter_increment(vm, d_idx, n)
@@ -1079,7 +1079,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": W.dtype, "data": "synthetic",
         "config": dict({"workload": W.name, "page_bytes": W.page, "frame_pool_bytes": W.pool,
-                        "policy": args.policy, "waves_in_flight": gv.gpuvm_max_waves(W.vm),
+                        "policy": args.policy, "waves_in_flight": (gv.gpuvm_max_waves_duplex if args.workload == "scatter" else gv.gpuvm_max_waves)(W.vm),
                         "oversubscription": round(W.arr.nbytes / W.pool, 2)}, **W.config()),
         "faults_per_s": round(st["faults"] / step_s, 1),
         "faults_per_step": st["faults"],

@@ -149,7 +149,12 @@ GPUVM_API int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats
 enum { GPUVM_WB_SERIAL = 0, GPUVM_WB_OVERLAPPED = 1 };
 GPUVM_API int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode);
 
-/* Wavefronts per compute unit the launchers aim for (1..32, default 8). */
+/* Wavefronts per compute unit the launchers aim for (1..32, default 8; a
+ * launch never uses more wavefronts than half the frames).  Left alone, the
+ * scatter-increment launcher, whose faults write back as much as they fetch,
+ * uses fewer: about 4 MiB of page traffic in flight, where the link's two
+ * directions together peak.  A value set here (or GPUVM_WAVES_PER_CU in the
+ * environment) is used as it is by every launcher. */
 GPUVM_API int gpuvm_set_waves_per_cu(gpuvm_t *vm, int waves_per_cu);
 
 /* Synchronise `stream` and return the first error a kernel recorded on this
@@ -160,6 +165,9 @@ GPUVM_API int gpuvm_check(gpuvm_t *vm, void *stream);
  * each wave holds at most one pinned page plus one frame under migration, so
  * it is min(n_frames / 2, what the device can hold). */
 GPUVM_API int gpuvm_max_waves(const gpuvm_t *vm);
+/* The same for the launchers whose faults write back as much as they fetch
+ * (gpuvm_run_scatter_increment); see gpuvm_set_waves_per_cu. */
+GPUVM_API int gpuvm_max_waves_duplex(const gpuvm_t *vm);
 
 /* Write every DIRTY page back to host_buf and clear the dirty bits; pages stay
  * resident (not in the paper, whose write-back happens only at eviction:

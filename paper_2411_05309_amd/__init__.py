@@ -73,6 +73,7 @@ _SIGNATURES = {
     "gpuvm_set_waves_per_cu": ([C.c_void_p, C.c_int], C.c_int),
     "gpuvm_check": ([C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_max_waves": ([C.c_void_p], C.c_int),
+    "gpuvm_max_waves_duplex": ([C.c_void_p], C.c_int),
     "gpuvm_flush": ([C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_reset": ([C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_stats": ([C.c_void_p, C.POINTER(Stats)], C.c_int),
@@ -191,6 +192,10 @@ def gpuvm_check(vm, stream=None):
 
 def gpuvm_max_waves(vm):
     return load().gpuvm_max_waves(vm)
+
+
+def gpuvm_max_waves_duplex(vm):
+    return load().gpuvm_max_waves_duplex(vm)
 
 
 def gpuvm_flush(vm, stream=None):

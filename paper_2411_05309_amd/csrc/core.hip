@@ -51,6 +51,19 @@ int launch_waves(const gpuvm_t *vm, size_t work_waves) {
     return (int)std::min(cap, need);
 }
 
+// For launches whose faults write back as much as they fetch.  With both
+// directions of the link busy, throughput peaks at about 4 MiB of page traffic
+// in flight (512 waves on 64 KiB pages, of which a wave has 8 KiB outstanding;
+// 1024 waves on 4 KiB pages) and is some 8 % lower with the 8-16 MiB that suit
+// one-way traffic.  A wave count chosen by the caller stands.
+int launch_waves_duplex(const gpuvm_t *vm, size_t work_waves) {
+    const int all = launch_waves(vm, work_waves);
+    if (vm->waves_chosen) return all;
+    const size_t per_wave = std::min<size_t>(vm->page_bytes, 8192);
+    const int sweet = (int)((4u << 20) / per_wave) / kWavesPerBlock * kWavesPerBlock;
+    return std::max(std::min(all, sweet), std::min(all, kWavesPerBlock));
+}
+
 extern "C" {
 
 const char *gpuvm_strerror(int code) {
@@ -110,7 +123,11 @@ int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_p
     }
     vm->cus = prop.multiProcessorCount;
     vm->waves_per_cu = 8;
-    if (const char *e = getenv("GPUVM_WAVES_PER_CU")) vm->waves_per_cu = std::max(1, std::min(32, atoi(e)));
+    vm->waves_chosen = false;
+    if (const char *e = getenv("GPUVM_WAVES_PER_CU")) {
+        vm->waves_per_cu = std::max(1, std::min(32, atoi(e)));
+        vm->waves_chosen = true;
+    }
     vm->page_bytes = page_bytes;
     gpuvm_dev_t &d = vm->dev;
     d.host = (char *)attr.devicePointer;
@@ -176,12 +193,18 @@ int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode) {
 int gpuvm_set_waves_per_cu(gpuvm_t *vm, int waves_per_cu) {
     if (!vm || waves_per_cu < 1 || waves_per_cu > 32) return GPUVM_EINVAL;
     vm->waves_per_cu = waves_per_cu;
+    vm->waves_chosen = true;
     return GPUVM_OK;
 }
 
 int gpuvm_max_waves(const gpuvm_t *vm) {
     if (!vm) return GPUVM_EINVAL;
     return launch_waves(vm, (size_t)1 << 40);
+}
+
+int gpuvm_max_waves_duplex(const gpuvm_t *vm) {
+    if (!vm) return GPUVM_EINVAL;
+    return launch_waves_duplex(vm, (size_t)1 << 40);
 }
 
 int gpuvm_flush(gpuvm_t *vm, void *stream) {

@@ -27,6 +27,7 @@ struct gpuvm {
     int device;
     int cus;
     int waves_per_cu;
+    bool waves_chosen;            // set by the caller (or the environment): launchers do not second-guess it
     size_t page_bytes;
     // deterministic mode scratch (allocated on first use)
     unsigned int *stamp = nullptr;        // [n_pages] phase tag of the last toucher
@@ -55,7 +56,8 @@ struct gpuvm {
 // Launch shape and kernel-side errors (core.hip).
 int check_kernel_error(gpuvm_t *vm);      // reads the error word a kernel may have recorded (synchronous copy)
 int grid_for_waves(int waves);            // workgroups for that many wavefronts
-int launch_waves(const gpuvm_t *vm, size_t work_waves);   // waves to keep in flight; 0 = pool too small
+int launch_waves(const gpuvm_t *vm, size_t work_waves);          // waves to keep in flight; 0 = pool too small
+int launch_waves_duplex(const gpuvm_t *vm, size_t work_waves);   // the same for launches that write back as much as they fetch
 
 // Fill kernels (a copy per translation unit; used instead of hipMemsetAsync so
 // that a caller may capture the launchers in a graph).

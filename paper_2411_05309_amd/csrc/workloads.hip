@@ -365,7 +365,7 @@ int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n, uint32_t *d_o
 int gpuvm_run_scatter_increment(gpuvm_t *vm, const uint32_t *d_idx, size_t n, void *stream) {
     if (!vm || (n && !d_idx)) return GPUVM_EINVAL;
     if (n == 0) return GPUVM_OK;
-    const int waves = launch_waves(vm, (n + 63) / 64);
+    const int waves = launch_waves_duplex(vm, (n + 63) / 64);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
     k_scatter_inc<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, vm->dev.bytes / 8);
     HIP_TRY(hipGetLastError());
