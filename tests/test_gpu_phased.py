@@ -62,6 +62,30 @@ def test_gather_phased_equals_sequential_replay(gpu, policy, n_elems, page, fram
         assert np.array_equal(b.arr, data)
 
 
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO])
+def test_embedding_shaped_page_sequence_equals_sequential_replay(gpu, policy):
+    """The embedding-bag configuration at reduced scale in deterministic mode: the
+    page sequence of its row reads (scrambled Zipf(1.05) ids, 512-byte rows, 128
+    rows per 64 KiB page, pool a quarter of the table, one bag of 32 rows per
+    phase) goes through the phased gather as one word per row; fault, hit and
+    eviction counts and the final frame table equal the sequential replay."""
+    rows, dim, page, bags, bag_len = 50_001, 128, 65536, 600, 32
+    table = inputs.f32_uniform(11, 0, rows * dim)
+    frames = (table.nbytes // 4) // page
+    ids = inputs.bag_row_ids(5, 0, bags * bag_len, rows, 1.05)
+    idx = (ids.astype(np.uint64) * dim).astype(np.uint32)                   # first word of each row
+    data = table.view(np.uint32)
+    want, want_sum = oracle.gather(data, idx)
+    sim = oracle.PagingSim(page // 8, frames, _POL[policy], n_words=-(-data.nbytes // 8))
+    sim.run((idx.astype(np.uint64) * 4) // 8, phase_len=bag_len)
+    with Backing(data, page, frames * page, policy) as b:
+        d_out = torch.zeros(idx.size, dtype=torch.int32, device="cuda")
+        gv.gpuvm_run_gather_phased(b.vm, dev(idx), idx.size, bag_len, d_out, None)
+        assert np.array_equal(host(d_out, np.uint32), want)
+        st = _compare_with_replay(b, sim, frames)
+        assert st["phases"] == bags and st["evictions"] > 0 and st["hits"] > 0
+
+
 @pytest.mark.parametrize("wb_mode", [gv.WB_OVERLAPPED, gv.WB_SERIAL])
 @pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_CLOCK_WRITE_AWARE])
 @pytest.mark.parametrize("n_elems,page,frames,n_upd,phase_len", [
