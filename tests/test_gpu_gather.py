@@ -30,6 +30,7 @@ def run_gather(b, idx, access_stats=False):
     ((1 << 18) + 1000, 4096, 16, 10007),   # short last page, ragged index count
     (1 << 16, 4096, 64, 4096),             # everything fits: compulsory misses only
     (1 << 20, 65536, 8, 70001),            # 64 KiB pages, tiny pool
+    (1 << 23, 1 << 20, 8, 20011),          # the largest page size (1 MiB), the smallest pool
 ])
 def test_gather_matches_oracle(gpu, policy, n_elems, page, frames, n_idx):
     data = inputs.u32_values(1, 0, n_elems)
