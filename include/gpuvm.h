@@ -212,6 +212,18 @@ GPUVM_API const char *gpuvm_strerror(int code);
 GPUVM_API int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n,
                                uint32_t *d_out, uint64_t *d_sum, void *stream);
 
+/* The gather above and the scatter-increment below for thread-per-element code
+ * with a condition around the access (the style of the paper's listing): element k takes part only if
+ * d_mask[k] != 0 (one byte per element, device memory), and only those lanes
+ * enter the accessors, so the fault path runs under arbitrary divergence.
+ *   gather:    out[k] = data[idx[k]] for the masked k; other out[k] untouched.
+ *   increment: data[idx[k]] += 1 (uint64 elements) for the masked k.
+ * Index bounds as for the unmasked forms (GPUVM_ERANGE from the kernel). */
+GPUVM_API int gpuvm_run_gather_masked(gpuvm_t *vm, const uint32_t *d_idx, const uint8_t *d_mask,
+                                      size_t n, uint32_t *d_out, void *stream);
+GPUVM_API int gpuvm_run_scatter_increment_masked(gpuvm_t *vm, const uint32_t *d_idx,
+                                                 const uint8_t *d_mask, size_t n, void *stream);
+
 /* The paper's vector-addition listing: C[i] = A[i] + B[i] for i < n over three
  * paged fp32 vectors (three handles, each with its own frame pool; A and B may
  * be the same handle, C must be distinct).  C is written with gpuvm_store, its

@@ -210,10 +210,9 @@ GPUVM_DEV void wave_copy(char *dst, const char *src, unsigned int bytes, const w
     copy_tier<4, LD, ST>(rd, rs, o, stride, vec_bytes);   /* 4 KiB page, full wave: one round          */
     copy_tier<2, LD, ST>(rd, rs, o, stride, vec_bytes);
     copy_tier<1, LD, ST>(rd, rs, o, stride, vec_bytes);
-    const unsigned int tail = bytes - vec_bytes;          /* < 16 */
-    if (w.rank < tail)
-        __builtin_amdgcn_raw_buffer_store_b8(__builtin_amdgcn_raw_buffer_load_b8(rs, vec_bytes + w.rank, 0, LD),
-                                             rd, vec_bytes + w.rank, 0, ST);
+    /* < 16 bytes left over (a short last page); the wave may have fewer active lanes than that */
+    for (unsigned int t = vec_bytes + w.rank; t < bytes; t += w.count)
+        __builtin_amdgcn_raw_buffer_store_b8(__builtin_amdgcn_raw_buffer_load_b8(rs, t, 0, LD), rd, t, 0, ST);
 }
 /* Whole-wave exchange for a fault whose victim is dirty: the old content of the
  * frame goes to `host_old` while the new page comes from `host_new`, with the

@@ -81,6 +81,8 @@ _SIGNATURES = {
     "gpuvm_dump_tables": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_strerror": ([C.c_int], C.c_char_p),
     "gpuvm_run_gather": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_run_gather_masked": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_run_scatter_increment_masked": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_prefetch": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_vector_add": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_run_vector_add_overwrite": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
@@ -229,6 +231,14 @@ def gpuvm_dump_tables(vm):
 
 def gpuvm_run_gather(vm, d_idx, n, d_out, d_sum=None, stream=None):
     _call("gpuvm_run_gather", vm, _ptr(d_idx), n, _ptr(d_out), _ptr(d_sum), _stream(stream))
+
+
+def gpuvm_run_gather_masked(vm, d_idx, d_mask, n, d_out, stream=None):
+    _call("gpuvm_run_gather_masked", vm, _ptr(d_idx), _ptr(d_mask), n, _ptr(d_out), _stream(stream))
+
+
+def gpuvm_run_scatter_increment_masked(vm, d_idx, d_mask, n, stream=None):
+    _call("gpuvm_run_scatter_increment_masked", vm, _ptr(d_idx), _ptr(d_mask), n, _stream(stream))
 
 
 def gpuvm_run_prefetch(vm, first_page, n_pages, stream=None):

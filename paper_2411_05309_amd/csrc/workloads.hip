@@ -47,6 +47,34 @@ __global__ __launch_bounds__(kBlock) void k_scatter_inc(gpuvm_dev_t vm, const ui
     }
 }
 
+// The accessors under divergence, as in thread-per-element code with a
+// condition around the access (the style of the paper's listing): only the
+// lanes whose mask byte is set enter gpuvm_load / gpuvm_atomic_add, so lookups,
+// faults and page copies run with whatever lanes happen to be active - down to
+// one - and the last wave of the grid is a partial one.
+__global__ __launch_bounds__(kBlock) void k_gather_masked(gpuvm_dev_t vm, const uint32_t *__restrict__ idx,
+                                                           const unsigned char *__restrict__ mask, size_t n,
+                                                           uint32_t *__restrict__ out, unsigned long long n_elems) {
+    const size_t nthreads = (size_t)gridDim.x * kBlock;
+    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n; k += nthreads) {
+        if (!mask[k]) continue;
+        const unsigned long long i = idx[k];
+        if (i >= n_elems) { raise_error(vm, GPUVM_ERANGE); continue; }
+        out[k] = gpuvm_load<uint32_t>(vm, i);
+    }
+}
+__global__ __launch_bounds__(kBlock) void k_scatter_inc_masked(gpuvm_dev_t vm, const uint32_t *__restrict__ idx,
+                                                                const unsigned char *__restrict__ mask, size_t n,
+                                                                unsigned long long n_elems) {
+    const size_t nthreads = (size_t)gridDim.x * kBlock;
+    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n; k += nthreads) {
+        if (!mask[k]) continue;
+        const unsigned long long i = idx[k];
+        if (i >= n_elems) { raise_error(vm, GPUVM_ERANGE); continue; }
+        gpuvm_atomic_add<unsigned long long>(vm, i, 1ull);
+    }
+}
+
 // The paper's own example (vector-addition listing): C[i] = A[i] + B[i] with all
 // three vectors paged; C is written through gpuvm_store, so its pages become
 // DIRTY and are written back at eviction or flush.
@@ -358,6 +386,30 @@ int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n, uint32_t *d_o
     k_gather<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, d_out,
                                                                          (unsigned long long *)d_sum,
                                                                          vm->dev.bytes / 4);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_gather_masked(gpuvm_t *vm, const uint32_t *d_idx, const uint8_t *d_mask, size_t n, uint32_t *d_out,
+                            void *stream) {
+    if (!vm || (n && (!d_idx || !d_mask || !d_out))) return GPUVM_EINVAL;
+    if (n == 0) return GPUVM_OK;
+    const int waves = launch_waves(vm, (n + 63) / 64);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    k_gather_masked<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, d_mask, n, d_out,
+                                                                                vm->dev.bytes / 4);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_run_scatter_increment_masked(gpuvm_t *vm, const uint32_t *d_idx, const uint8_t *d_mask, size_t n,
+                                       void *stream) {
+    if (!vm || (n && (!d_idx || !d_mask))) return GPUVM_EINVAL;
+    if (n == 0) return GPUVM_OK;
+    const int waves = launch_waves_duplex(vm, (n + 63) / 64);
+    if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
+    k_scatter_inc_masked<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, d_mask, n,
+                                                                                     vm->dev.bytes / 8);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }
