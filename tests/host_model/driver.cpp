@@ -1,6 +1,6 @@
 // Protocol stress of the fault path on the CPU: N threads, each a one-lane
 // wavefront, run seeded random loads, atomic adds, stores, optimistic page
-// reads and fault-ahead touches through the accessors of gpuvm_device.h (the
+// reads, page-level pinned writes and fault-ahead touches through the accessors of gpuvm_device.h (the
 // header itself, compiled for the host through shim.h) over a pool far smaller
 // than the data set.  Checked while running: a counter never reads below the
 // increments that had completed before the read began nor above those that had
@@ -87,9 +87,17 @@ int main(int argc, char **argv) {
                 continue;
             }
             if (owner_of(i) >= 0) continue;                       // shared operations leave private elements alone
-            if (op <= 2) {                                        // increment
+            if (op <= 1) {                                        // increment through the element accessor
                 announced[i].fetch_add(1);
                 gpuvm_atomic_add<u64>(vm, i, 1ull);
+                completed[i].fetch_add(1);
+            } else if (op == 2) {                                 // increment by a page-level writer (pinned)
+                const unsigned page = (unsigned)((i * 8) >> shift);
+                announced[i].fetch_add(1);
+                char *p = gpuvm_acquire(vm, page, true);
+                __hip_atomic_fetch_add(reinterpret_cast<u64 *>(p + ((i * 8) & (page_bytes - 1))), 1ull, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                gpuvm_release(vm, page);
                 completed[i].fetch_add(1);
             } else if (op <= 4) {                                 // read through the element accessor
                 const u64 lo = completed[i].load();
