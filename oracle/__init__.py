@@ -22,7 +22,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gpuvm_oracle.c")
 _LIB = os.path.join(_HERE, "libgpuvm_oracle.so")
 
-FIFO, CLOCK, CLOCK_WA = 0, 1, 3
+FIFO, CLOCK, CLOCK_WA, GCLOCK = 0, 1, 3, 4
 READ, WRITE, ADD = 0, 1, 2
 COUNTER_NAMES = ("faults", "hits", "evictions", "writebacks_evict",
                  "writebacks_flush", "skips", "sweeps", "phases")
@@ -245,7 +245,8 @@ def filter_sum(key, val, threshold):
 
 class PagingSim:
     """Sequential simulator of the circular frame buffer with reference
-    counters; FIFO or CLOCK.  ``host`` (uint64 array, modified in place by
+    counters; policy FIFO, CLOCK, CLOCK_WA (write-aware) or GCLOCK (use count
+    0..2).  ``host`` (uint64 array, modified in place by
     write-backs) is optional: without it only the bookkeeping is simulated and
     ``n_words`` gives the size of the address space in 8-byte words."""
 

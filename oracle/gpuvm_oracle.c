@@ -32,6 +32,11 @@
  *     - the write-aware CLOCK variant (the paper only names the idea: delay
  *       the eviction of write-intensive pages) passes over a dirty page once
  *       more after its reference bit is clear, then evicts it;
+ *     - the generalized CLOCK variant (not in the paper; the classical GCLOCK
+ *       with a small counter) keeps a use count of 0..2 instead of the bit:
+ *       installed at 0, raised by every later use, lowered by the passing
+ *       cursor, evicted at 0 - pages earn their chances by being used again,
+ *       and a scan never makes the cursor pass anything;
  *     - accesses arrive in phases (a group of accesses that are in flight
  *       together); each distinct page of a phase counts one hit or one fault;
  *       its faults are served in ascending page order; pins are dropped when
@@ -270,7 +275,17 @@ void oracle_scatter_increment(uint64_t *host, const uint32_t *idx, uint64_t k)
 /* Part 2: sequential paged-memory simulator                           */
 /* ------------------------------------------------------------------ */
 
-enum { SIM_FIFO = 0, SIM_CLOCK = 1, SIM_CLOCK_WA = 3 };   /* 2 (wait for the drawn frame) has no sequential meaning */
+enum { SIM_FIFO = 0, SIM_CLOCK = 1, SIM_CLOCK_WA = 3, SIM_GCLOCK = 4 };   /* 2 (wait for the drawn frame) has no sequential meaning */
+
+/* SIM_GCLOCK: generalized CLOCK with a use count of 0..2 per frame, kept in the
+ * two flag bytes ref (count >= 1) and defer (count == 2).  A page is installed
+ * with count 0, every later use raises the count by one up to 2, the hand
+ * lowers a positive count by one and passes, and takes a frame at count 0. */
+static void sim_mark_used(uint8_t *ref, uint8_t *defer, int policy)
+{
+    if (policy == SIM_GCLOCK && *ref) *defer = 1;
+    *ref = 1;
+}
 enum { SIM_READ = 0, SIM_WRITE = 1, SIM_ADD = 2 };
 enum {
     SIM_C_FAULTS = 0, SIM_C_HITS, SIM_C_EVICTIONS, SIM_C_WB_EVICT,
@@ -316,7 +331,7 @@ sim_t *sim_create(uint64_t *host, uint64_t n_words, uint64_t page_words,
     s->where = (int64_t *)malloc(s->n_pages * sizeof(int64_t));
     s->seen = (uint8_t *)calloc(s->n_pages, 1);
     s->frames = host ? (uint64_t *)calloc(n_frames * page_words, 8) : NULL;
-    if (policy != SIM_FIFO && policy != SIM_CLOCK && policy != SIM_CLOCK_WA) { sim_destroy(s); return NULL; }
+    if (policy != SIM_FIFO && policy != SIM_CLOCK && policy != SIM_CLOCK_WA && policy != SIM_GCLOCK) { sim_destroy(s); return NULL; }
     if (!s->owner || !s->ref || !s->dirty || !s->defer || !s->pin || !s->where || !s->seen ||
         (host && !s->frames)) { sim_destroy(s); return NULL; }
     for (uint64_t f = 0; f < n_frames; ++f) s->owner[f] = -1;
@@ -353,6 +368,10 @@ static void sim_fault(sim_t *s, uint64_t p)
         if (s->policy == SIM_CLOCK_WA && s->dirty[f] && !s->defer[f]) {
             s->defer[f] = 1; s->counters[SIM_C_SWEEPS]++; continue;   /* spare a written page once */
         }
+        if (s->policy == SIM_GCLOCK && (s->defer[f] || s->ref[f])) {  /* count 2 -> 1 -> 0 */
+            if (s->defer[f]) s->defer[f] = 0; else s->ref[f] = 0;
+            s->counters[SIM_C_SWEEPS]++; continue;
+        }
         uint64_t q = (uint64_t)s->owner[f];
         s->counters[SIM_C_EVICTIONS]++;
         if (s->dirty[f]) {
@@ -366,7 +385,7 @@ static void sim_fault(sim_t *s, uint64_t p)
     }
     s->owner[f] = (int64_t)p;
     s->where[p] = (int64_t)f;
-    s->dirty[f] = 0; s->defer[f] = 0; s->ref[f] = 1; s->pin[f] = 1;
+    s->dirty[f] = 0; s->defer[f] = 0; s->ref[f] = s->policy == SIM_GCLOCK ? 0 : 1; s->pin[f] = 1;
     if (s->host)
         memcpy(s->frames + f * s->page_words, s->host + p * s->page_words,
                page_len(s, p) * 8);
@@ -396,7 +415,7 @@ int sim_phase(sim_t *s, const uint64_t *word_idx, const uint8_t *op,
     /* pages already in GPU memory: one more user each, marked as used */
     for (uint64_t i = 0; i < nu; ++i) {
         int64_t f = s->where[pages[i]];
-        if (f >= 0) { s->pin[f]++; s->ref[f] = 1; s->counters[SIM_C_HITS]++; s->seen[pages[i]] = 2; }
+        if (f >= 0) { s->pin[f]++; sim_mark_used(&s->ref[f], &s->defer[f], s->policy); s->counters[SIM_C_HITS]++; s->seen[pages[i]] = 2; }
     }
     /* missing pages, ascending */
     for (uint64_t i = 0; i < nu; ++i) {

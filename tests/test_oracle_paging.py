@@ -434,6 +434,92 @@ def test_write_aware_clock_spares_the_written_page():
     assert wa.counters["writebacks_evict"] == 1 and sorted(wa.state()["owner"].tolist()) == [3, 4]
 
 
+# ---------------------------------------------------------------- generalized CLOCK (use count 0..2)
+
+def gclock_queue_model(refs, frames, cap=2):
+    """Written independently of the simulator: resident pages in a queue, each
+    with a use count that starts at 0 and grows by one per later use up to `cap`;
+    to make room the front page is re-appended with its count lowered while the
+    count is positive, and leaves at 0.  Returns faults, passes, resident set."""
+    q, cnt = deque(), {}
+    faults = passes = 0
+    for p in refs:
+        if p in cnt:
+            cnt[p] = min(cnt[p] + 1, cap)
+            continue
+        faults += 1
+        if len(q) == frames:
+            while True:
+                old = q.popleft()
+                if cnt[old] > 0:
+                    cnt[old] -= 1
+                    passes += 1
+                    q.append(old)
+                else:
+                    del cnt[old]
+                    break
+        q.append(p)
+        cnt[p] = 0
+    return faults, passes, set(q)
+
+
+def test_gclock_against_queue_model_exhaustive_and_random():
+    for npages, frames, length in [(4, 2, 7), (4, 3, 7), (5, 3, 6)]:
+        for refs in itertools.product(range(npages), repeat=length):
+            f, passes, resident = gclock_queue_model(refs, frames)
+            sim = _run_pages(list(refs), frames, oracle.GCLOCK, n_pages=npages)
+            own = sim.state()["owner"]
+            assert (sim.counters["faults"], sim.counters["sweeps"], set(own[own >= 0].tolist())) == (f, passes, resident), refs
+    rng = np.random.default_rng(31)
+    for _ in range(60):
+        npages = int(rng.integers(4, 40))
+        frames = int(rng.integers(1, npages))
+        refs = np.minimum(rng.geometric(0.12, 2000) - 1, npages - 1).tolist()
+        f, passes, resident = gclock_queue_model(refs, frames)
+        sim = _run_pages(refs, frames, oracle.GCLOCK, n_pages=npages)
+        own = sim.state()["owner"]
+        assert (sim.counters["faults"], sim.counters["sweeps"], set(own[own >= 0].tolist())) == (f, passes, resident)
+
+
+def test_gclock_is_fifo_without_reuse_and_never_sweeps_on_a_scan():
+    # pages are installed with count 0: a cyclic scan (no page used again while
+    # resident) takes every frame at the hand's first visit - FIFO's faults,
+    # evictions and placement, and not one pass
+    for n, frames, turns in [(10, 3, 4), (64, 16, 3), (7, 6, 5)]:
+        refs = list(range(n)) * turns
+        g = _run_pages(refs, frames, oracle.GCLOCK)
+        f = _run_pages(refs, frames, FIFO)
+        assert g.counters["faults"] == f.counters["faults"] == turns * n
+        assert g.counters["evictions"] == turns * n - frames and g.counters["sweeps"] == 0
+        assert g.state()["owner"].tolist() == f.state()["owner"].tolist()
+    # CLOCK pays one pass per eviction on the same scan (every bit is set at install)
+    c = _run_pages(list(range(10)) * 4, 3, CLOCK)
+    assert c.counters["sweeps"] > 0
+
+
+def test_gclock_hand_worked_trace():
+    # 2 frames, trace 1 1 1 2 3 4 5.  Page 1 is used twice more after its install:
+    # count 2 (the cap).  3 faults: frame 0 (page 1) 2 -> 1, passed; frame 1 (page 2,
+    # count 0) taken.  4 faults: page 1 1 -> 0, passed; page 3 taken.  5 faults: page 1
+    # at 0, taken.  Two earned chances, two passes, then it goes.
+    sim = _run_pages([1, 1, 1, 2, 3], 2, oracle.GCLOCK, n_pages=6)
+    assert sim.state()["owner"].tolist() == [1, 3] and sim.counters["sweeps"] == 1
+    st = sim.state()
+    assert (int(st["ref"][0]), int(st["defer"][0])) == (1, 0)                 # count 1
+    sim.run(np.array([4], np.uint64))
+    assert sim.state()["owner"].tolist() == [1, 4] and sim.counters["sweeps"] == 2
+    sim.run(np.array([5], np.uint64))
+    assert sim.state()["owner"].tolist() == [5, 4] and sim.counters["sweeps"] == 2
+    assert sim.counters["faults"] == 5 and sim.counters["hits"] == 2 and sim.counters["evictions"] == 3
+    # CLOCK on the first five references: both bits are set at install, the hand
+    # clears them in turn and takes page 1, the one that was used three times
+    ck = _run_pages([1, 1, 1, 2, 3], 2, CLOCK, n_pages=6)
+    assert ck.state()["owner"].tolist() == [3, 2] and ck.counters["sweeps"] == 2
+    # the count is capped: ten uses earn no more than two passes
+    many = _run_pages([1] * 10 + [2, 3, 4, 5], 2, oracle.GCLOCK, n_pages=6)
+    assert 1 not in many.state()["owner"].tolist() and many.counters["sweeps"] == 2
+
+
 def test_waiting_policy_has_no_sequential_replay():
     with pytest.raises(ValueError):
         PagingSim(1, 4, 2, n_words=8)
