@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "matvec", "filter", "vector_add", "vector_add_overwrite", "embedding", "scatter"])
-    ap.add_argument("--policy", default="clock", choices=["clock", "fifo", "fifo_wait"])
+    ap.add_argument("--policy", default="clock", choices=["clock", "fifo", "fifo_wait", "clock_write_aware", "gclock"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
@@ -934,7 +934,7 @@ def sweep_policy(gv, torch, np, inputs, oracle):
     d_r = [torch.from_numpy(x.view(np.int32)).cuda() for x in r_idx]
     d_out = torch.zeros((rounds, reads), dtype=torch.int32, device="cuda")
     for name, pol in (("fifo", gv.POLICY_FIFO), ("fifo_wait", gv.POLICY_FIFO_WAIT), ("clock", gv.POLICY_CLOCK),
-                      ("clock_write_aware", gv.POLICY_CLOCK_WRITE_AWARE)):
+                      ("clock_write_aware", gv.POLICY_CLOCK_WRITE_AWARE), ("gclock", gv.POLICY_GCLOCK)):
         arr[...] = 0
         vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, pool, pol)
         torch.cuda.synchronize()
@@ -1013,7 +1013,8 @@ def main():
     gv.load()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    policy = {"clock": gv.POLICY_CLOCK, "fifo": gv.POLICY_FIFO, "fifo_wait": gv.POLICY_FIFO_WAIT}[args.policy]
+    policy = {"clock": gv.POLICY_CLOCK, "fifo": gv.POLICY_FIFO, "fifo_wait": gv.POLICY_FIFO_WAIT,
+              "clock_write_aware": gv.POLICY_CLOCK_WRITE_AWARE, "gclock": gv.POLICY_GCLOCK}[args.policy]
 
     if args.sweep:
         import oracle

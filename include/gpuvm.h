@@ -50,6 +50,13 @@ enum {
                                go first and written ones are written back less often
                                (paper: Comparisons with UVM - "delay its eviction and
                                evict one of the least needed read-intensive pages")   */
+    GPUVM_POLICY_GCLOCK = 4, /* generalized CLOCK (not in the paper; the classical GCLOCK
+                               with a small counter): a use count of 0..2 per page
+                               instead of the bit - installed at 0, raised by every
+                               later use, lowered by the passing hand, evicted at 0.
+                               Pages earn their chances by being used again, so
+                               one-time pages leave first, and a scan never makes
+                               the hand pass anything                               */
     GPUVM_POLICY_FIFO_WAIT = 2 /* FIFO, but a leader that draws a frame in use waits
                                (bounded) for its reference counter to reach zero, as
                                the paper words it, instead of passing the frame over;
@@ -120,7 +127,7 @@ GPUVM_API int gpuvm_host_free(void *p);
  *   page_bytes        power of two, 4 KiB .. 1 MiB; every element a launcher
  *                     accesses must not straddle a page.
  *   frame_pool_bytes  HBM budget; n_frames = floor(frame_pool_bytes/page_bytes) >= 2.
- *   policy            GPUVM_POLICY_FIFO, _CLOCK, _CLOCK_WRITE_AWARE or _FIFO_WAIT.
+ *   policy            GPUVM_POLICY_FIFO, _CLOCK, _CLOCK_WRITE_AWARE, _GCLOCK or _FIFO_WAIT.
  * Allocates (hipMalloc) the frame pool, page table (8 B per page), frame table
  * (4 B per frame) and counters; all pages start INVALID, all frames empty, the
  * ring cursor at 0. */

@@ -71,7 +71,8 @@
 #define GPUVM_PTE_DIRTY       (1ull << 33)
 #define GPUVM_PTE_STATE_SHIFT 34
 #define GPUVM_PTE_STATE_MASK  (3ull << GPUVM_PTE_STATE_SHIFT)
-#define GPUVM_PTE_DEFER       (1ull << 36)   /* write-aware CLOCK: dirty page already spared once */
+#define GPUVM_PTE_DEFER       (1ull << 36)   /* write-aware CLOCK: dirty page already spared once;
+                                                 generalized CLOCK: second bit of the use count    */
 #define GPUVM_PTE_FRAME_SHIFT 37
 #define GPUVM_ST_INVALID  0ull
 #define GPUVM_ST_LOADING  1ull
@@ -89,6 +90,15 @@ enum {
 
 __device__ __forceinline__ bool gpuvm_uses_ref(unsigned int policy) {
     return policy == GPUVM_POLICY_CLOCK || policy == GPUVM_POLICY_CLOCK_WRITE_AWARE;
+}
+/* What a use of a resident page adds to its word: the reference bit under the
+ * CLOCK policies; under the generalized CLOCK one step of the use count, which
+ * is the number of set bits among REF and DEFER (0..2), so that uses and the
+ * hand can race without ever producing a meaningless combination. */
+__device__ __forceinline__ unsigned long long gpuvm_use_mark(unsigned int policy, unsigned long long word) {
+    if (policy == GPUVM_POLICY_GCLOCK)
+        return !(word & GPUVM_PTE_REF) ? GPUVM_PTE_REF : !(word & GPUVM_PTE_DEFER) ? GPUVM_PTE_DEFER : 0ull;
+    return gpuvm_uses_ref(policy) && !(word & GPUVM_PTE_REF) ? GPUVM_PTE_REF : 0ull;
 }
 
 namespace gpuvm_detail {
@@ -294,6 +304,11 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
                 ++sweeps;
                 continue;
             }
+            if (vm.policy == GPUVM_POLICY_GCLOCK && (pq & (GPUVM_PTE_REF | GPUVM_PTE_DEFER))) {
+                a_and(vm.pte + q, ~((pq & GPUVM_PTE_DEFER) ? GPUVM_PTE_DEFER : GPUVM_PTE_REF));   /* count - 1 */
+                ++sweeps;
+                continue;
+            }
             if (vm.policy == GPUVM_POLICY_CLOCK_WRITE_AWARE && (pq & GPUVM_PTE_DIRTY) && !(pq & GPUVM_PTE_DEFER)) {
                 /* a written page costs a write-back: spare it once and look for a
                  * clean victim first (a CAS: without a pin the page may leave) */
@@ -350,7 +365,8 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
          * LOADING, so one xor moves state, frame, flags and generation at once */
         const unsigned long long flip =
             ((GPUVM_ST_LOADING ^ GPUVM_ST_RESIDENT) << GPUVM_PTE_STATE_SHIFT) |
-            ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) | GPUVM_PTE_REF |
+            ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) |
+            (vm.policy == GPUVM_POLICY_GCLOCK ? 0ull : GPUVM_PTE_REF) |    /* use count 0 there */
             (write ? GPUVM_PTE_DIRTY : 0ull) |
             ((unsigned long long)(gen ^ ((gen + 1u) & 0xFFFu)) << GPUVM_PTE_GEN_SHIFT);
         a_xor(vm.pte + page, flip);                           /* publish: RESIDENT */
@@ -399,7 +415,7 @@ GPUVM_DEV char *acquire_page(const gpuvm_dev_t &vm, unsigned int page_any, bool 
         if (w.leader) {
             unsigned long long need = 0;
             if (write && !(cur & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
-            if (gpuvm_uses_ref(vm.policy) && !(cur & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
+            need |= gpuvm_use_mark(vm.policy, cur);
             if (need) a_or(pte, need);
             if (vm.flags & GPUVM_F_ACCESS_STATS) stat_add(vm, GPUVM_S_HITS, 1);
         }
@@ -477,9 +493,10 @@ __device__ __forceinline__ bool gpuvm_peek_same(const gpuvm_dev_t &vm, unsigned 
     using namespace gpuvm_detail;
     const bool same = ((again ^ token) & GPUVM_PTE_IDENT_MASK) == 0 &&
                       ((token & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
-    if (same && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF) && wave_now().leader) {
-        unsigned long long expect = again;                    /* second-chance bit, best effort */
-        a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
+    const unsigned long long mark = same ? gpuvm_use_mark(vm.policy, again) : 0ull;
+    if (mark && wave_now().leader) {
+        unsigned long long expect = again;                    /* second-chance bit / use count, best effort */
+        a_cas(vm.pte + page, &expect, again | mark);
     }
     if (same && (vm.flags & GPUVM_F_ACCESS_STATS) && wave_now().leader) stat_add(vm, GPUVM_S_HITS, 1);
     return same;
@@ -544,9 +561,10 @@ GPUVM_DEV unsigned int count_page_groups(unsigned int page, bool want) {
 GPUVM_DEV bool optimistic_read_stands(const gpuvm_dev_t &vm, unsigned int page, unsigned long long word,
                                       unsigned long long again, bool may_mark) {
     const bool still = ((again ^ word) & GPUVM_PTE_IDENT_MASK) == 0;
-    if (still && may_mark && gpuvm_uses_ref(vm.policy) && !(again & GPUVM_PTE_REF)) {
+    const unsigned long long mark = still && may_mark ? gpuvm_use_mark(vm.policy, again) : 0ull;
+    if (mark) {
         unsigned long long expect = again;
-        a_cas(vm.pte + page, &expect, again | GPUVM_PTE_REF);
+        a_cas(vm.pte + page, &expect, again | mark);
     }
     return still;
 }
@@ -669,7 +687,7 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
             if (resident) {
                 unsigned long long need = 0;
                 if (!(word & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
-                if (gpuvm_uses_ref(vm.policy) && !(word & GPUVM_PTE_REF)) need |= GPUVM_PTE_REF;
+                need |= gpuvm_use_mark(vm.policy, word);
                 if (need) a_or(vm.pte + page, need);
             }
             a_add(vm.pte + page, ~0ull);                      /* unpin, or give the pin back */

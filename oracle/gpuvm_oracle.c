@@ -466,7 +466,7 @@ void sim_flush(sim_t *s)
                 memcpy(s->host + q * s->page_words, s->frames + f * s->page_words,
                        page_len(s, q) * 8);
             s->dirty[f] = 0;
-            s->defer[f] = 0;
+            if (s->policy != SIM_GCLOCK) s->defer[f] = 0;   /* there it is half of the use count */
         }
     }
 }

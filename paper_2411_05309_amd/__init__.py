@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgpuvm.so")
 
 OK, EINVAL, ENOMEM, EPIN, EDEADLK, EHIP, ERANGE = 0, -1, -2, -3, -4, -5, -6
-POLICY_FIFO, POLICY_CLOCK, POLICY_FIFO_WAIT, POLICY_CLOCK_WRITE_AWARE = 0, 1, 2, 3
+POLICY_FIFO, POLICY_CLOCK, POLICY_FIFO_WAIT, POLICY_CLOCK_WRITE_AWARE, POLICY_GCLOCK = 0, 1, 2, 3, 4
 WB_SERIAL, WB_OVERLAPPED = 0, 1
 STAT_NAMES = ("faults", "evictions", "writebacks_evict", "writebacks_flush",
               "bytes_in", "bytes_out", "hits", "wave_page_groups",

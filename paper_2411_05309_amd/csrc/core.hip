@@ -26,7 +26,9 @@ __global__ __launch_bounds__(kBlock) void k_flush(gpuvm_dev_t vm) {
         const unsigned int len = page_len(vm, q);
         copy_frame_to_host(vm.host + ((size_t)q << vm.page_shift), vm.frames + ((size_t)f << vm.page_shift), len, w);
         if (w.leader) {
-            a_and(vm.pte + q, ~(GPUVM_PTE_DIRTY | GPUVM_PTE_DEFER));
+            // the write-aware policy's 'spared once' mark goes with the dirty bit; under the
+            // generalized CLOCK the same bit is half of the use count and stays
+            a_and(vm.pte + q, ~(GPUVM_PTE_DIRTY | (vm.policy == GPUVM_POLICY_GCLOCK ? 0ull : GPUVM_PTE_DEFER)));
             stat_add(vm, GPUVM_S_WB_FLUSH, 1);
             stat_add(vm, GPUVM_S_BYTES_OUT, len);
         }
@@ -99,7 +101,7 @@ int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_p
     *out = nullptr;
     if (!host_buf || bytes == 0) return GPUVM_EINVAL;
     if (page_bytes < 4096 || page_bytes > (1u << 20) || (page_bytes & (page_bytes - 1))) return GPUVM_EINVAL;
-    if (policy < GPUVM_POLICY_FIFO || policy > GPUVM_POLICY_CLOCK_WRITE_AWARE) return GPUVM_EINVAL;
+    if (policy < GPUVM_POLICY_FIFO || policy > GPUVM_POLICY_GCLOCK) return GPUVM_EINVAL;
     const size_t n_frames = frame_pool_bytes / page_bytes;
     const size_t n_pages = (bytes + page_bytes - 1) / page_bytes;
     if (n_frames < 2 || n_frames >= (1u << 27) || n_pages >= 0xFFFFFFFFull) return GPUVM_EINVAL;

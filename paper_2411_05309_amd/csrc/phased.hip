@@ -23,7 +23,9 @@ __global__ __launch_bounds__(kBlock) void k_phase_lookup(gpuvm_dev_t vm, const u
     const unsigned long long pq = a_load(vm.pte + page);
     if (((pq & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT) {
         a_add(vm.pte + page, 1ull);                                   // one more user
-        if (!(pq & GPUVM_PTE_REF)) a_or(vm.pte + page, GPUVM_PTE_REF);
+        const unsigned long long mark = vm.policy == GPUVM_POLICY_GCLOCK ? gpuvm_use_mark(vm.policy, pq)
+                                                                           : (pq & GPUVM_PTE_REF) ? 0ull : GPUVM_PTE_REF;
+        if (mark) a_or(vm.pte + page, mark);                          // used: reference bit / use count
         atomicAdd(ctr + 1, 1u);
     } else {
         miss[atomicAdd(ctr + 0, 1u)] = page;
@@ -66,6 +68,11 @@ __global__ __launch_bounds__(1024) void k_phase_assign(gpuvm_dev_t vm, const uns
                 st[GPUVM_S_SWEEPS] += 1;
                 continue;
             }
+            if (vm.policy == GPUVM_POLICY_GCLOCK && (pq & (GPUVM_PTE_REF | GPUVM_PTE_DEFER))) {
+                vm.pte[q] = pq & ~((pq & GPUVM_PTE_DEFER) ? GPUVM_PTE_DEFER : GPUVM_PTE_REF);   // use count - 1
+                st[GPUVM_S_SWEEPS] += 1;
+                continue;
+            }
             if (vm.policy == GPUVM_POLICY_CLOCK_WRITE_AWARE && (pq & GPUVM_PTE_DIRTY) && !(pq & GPUVM_PTE_DEFER)) {
                 vm.pte[q] = pq | GPUVM_PTE_DEFER;
                 st[GPUVM_S_SWEEPS] += 1;
@@ -80,7 +87,8 @@ __global__ __launch_bounds__(1024) void k_phase_assign(gpuvm_dev_t vm, const uns
         }
         vm.frame_owner[f] = p;
         vm.pte[p] = (GPUVM_ST_RESIDENT << GPUVM_PTE_STATE_SHIFT) | ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) |
-                    GPUVM_PTE_REF | ((vm.pte[p] + (1ull << GPUVM_PTE_GEN_SHIFT)) & GPUVM_PTE_GEN_MASK) |
+                    (vm.policy == GPUVM_POLICY_GCLOCK ? 0ull : GPUVM_PTE_REF) |
+                    ((vm.pte[p] + (1ull << GPUVM_PTE_GEN_SHIFT)) & GPUVM_PTE_GEN_MASK) |
                     1ull;                                             // next generation, pinned once
         st[GPUVM_S_FAULTS] += 1;
         st[GPUVM_S_BYTES_IN] += page_len(vm, p);

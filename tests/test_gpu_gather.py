@@ -24,7 +24,7 @@ def run_gather(b, idx, access_stats=False):
     return host(d_out, np.uint32)[:idx.size], int(host(d_sum, np.uint64)[0])
 
 
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT])
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT, gv.POLICY_GCLOCK])
 @pytest.mark.parametrize("n_elems,page,frames,n_idx", [
     (1 << 18, 4096, 64, 1 << 15),          # 256 pages over 64 frames
     ((1 << 18) + 1000, 4096, 16, 10007),   # short last page, ragged index count

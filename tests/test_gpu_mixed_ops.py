@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("wb_mode", [gv.WB_SERIAL, gv.WB_OVERLAPPED])
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT, gv.POLICY_CLOCK_WRITE_AWARE])
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT, gv.POLICY_CLOCK_WRITE_AWARE, gv.POLICY_GCLOCK])
 @pytest.mark.parametrize("n64,page,frames,seed", [
     ((1 << 16) + 37, 4096, 24, 1),       # 129 pages (the last one short) over 24 frames
     (1 << 17, 65536, 8, 2),              # 16 pages of 64 KiB over the smallest pool

@@ -13,7 +13,8 @@ from gpu_util import Backing, check_invariants, dev, host
 
 pytestmark = pytest.mark.gpu
 
-_POL = {gv.POLICY_FIFO: oracle.FIFO, gv.POLICY_CLOCK: oracle.CLOCK, gv.POLICY_CLOCK_WRITE_AWARE: oracle.CLOCK_WA}
+_POL = {gv.POLICY_FIFO: oracle.FIFO, gv.POLICY_CLOCK: oracle.CLOCK, gv.POLICY_CLOCK_WRITE_AWARE: oracle.CLOCK_WA,
+        gv.POLICY_GCLOCK: oracle.GCLOCK}
 
 
 def _compare_with_replay(b, sim, frames):
@@ -35,7 +36,7 @@ def _compare_with_replay(b, sim, frames):
     return st
 
 
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO])
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_GCLOCK])
 @pytest.mark.parametrize("n_elems,page,frames,n_idx,phase_len", [
     (1 << 18, 4096, 64, 20000, 48),        # 256 pages over 64 frames, phases pin most of the pool
     ((1 << 16) + 100, 4096, 16, 5003, 7),  # short last page, ragged last phase
@@ -62,7 +63,7 @@ def test_gather_phased_equals_sequential_replay(gpu, policy, n_elems, page, fram
         assert np.array_equal(b.arr, data)
 
 
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO])
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_GCLOCK])
 def test_embedding_shaped_page_sequence_equals_sequential_replay(gpu, policy):
     """The embedding-bag configuration at reduced scale in deterministic mode: the
     page sequence of its row reads (scrambled Zipf(1.05) ids, 512-byte rows, 128
@@ -87,7 +88,7 @@ def test_embedding_shaped_page_sequence_equals_sequential_replay(gpu, policy):
 
 
 @pytest.mark.parametrize("wb_mode", [gv.WB_OVERLAPPED, gv.WB_SERIAL])
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_CLOCK_WRITE_AWARE])
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_CLOCK_WRITE_AWARE, gv.POLICY_GCLOCK])
 @pytest.mark.parametrize("n_elems,page,frames,n_upd,phase_len", [
     (1 << 15, 4096, 16, 20000, 12),
     ((1 << 14) + 9, 4096, 8, 6001, 5),

@@ -128,7 +128,7 @@ def test_embedding_bag(gpu, dim, rows, page, frames, bags, bag_len):
 # ---------------------------------------------------------------- scatter-increment
 
 @pytest.mark.parametrize("wb_mode", [gv.WB_OVERLAPPED, gv.WB_SERIAL])
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT, gv.POLICY_CLOCK_WRITE_AWARE])
+@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT, gv.POLICY_CLOCK_WRITE_AWARE, gv.POLICY_GCLOCK])
 @pytest.mark.parametrize("n_elems,page,frames,n_upd", [
     (1 << 17, 4096, 32, 200000),            # 256 pages over 32 frames: dirty evictions
     ((1 << 15) + 77, 4096, 16, 50001),      # short last page

@@ -38,7 +38,7 @@ def driver(tmp_path_factory):
     return str(exe)
 
 
-POLICIES = {"fifo": 0, "clock": 1, "fifo_wait": 2, "clock_write_aware": 3}
+POLICIES = {"fifo": 0, "clock": 1, "fifo_wait": 2, "clock_write_aware": 3, "gclock": 4}
 
 
 @pytest.mark.parametrize("wb_mode", [0, 1])
