@@ -17,8 +17,10 @@
  *     gpuvm_release(vm, page);
  *
  * Execution model.  A CDNA wavefront has no independent thread scheduling, so
- * the fault path is wave-uniform: the accessor loops over the distinct pages
- * its active lanes touch (wavefront dedup, paper: Page access
+ * the fault path is wave-uniform: reads of resident pages are served lane by
+ * lane without any reference count (optimistic, validated by the page's
+ * word); for writes and for whatever missed, the accessor loops over the
+ * distinct pages its active lanes touch (wavefront dedup, paper: Page access
  * synchronization); for each page the first lane of the group is the leader
  * and performs every atomic, and all active lanes move the page together (the
  * substitute for the paper's NIC work request).  While it waits or allocates
@@ -31,10 +33,11 @@
  * leave the pin count of concurrent users intact):
  *     bits  0..19  pin    reference counter: waves that use or wait for the page
  *     bits 20..31  gen    install generation, +1 every time the page becomes RESIDENT
- *     bit   32     REF    CLOCK reference bit
+ *     bit   32     REF    CLOCK reference bit (generalized CLOCK: first bit of the use count)
  *     bit   33     DIRTY  frame differs from host memory
  *     bits 34..35  state  0 INVALID, 1 LOADING, 2 RESIDENT, 3 EVICTING
  *     bit   36     DEFER  write-aware CLOCK: the hand has spared this dirty page once
+ *                         (generalized CLOCK: second bit of the use count)
  *     bits 37..63  frame  valid while RESIDENT / EVICTING
  * Frame table: frame_owner[f] = page whose data the frame holds (0xFFFFFFFF
  * before first use).  hand[0] is the global head cursor of the frame ring;
