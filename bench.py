@@ -132,7 +132,7 @@ class GatherWorkload:
 
     def cpu_baseline(self, oracle):
         reps, t = 0, 0.0
-        while t < 1.0 and reps < 200:
+        while t < 10.0 and reps < 5000:                 # about ten seconds of CPU work
             t0 = time.perf_counter()
             oracle.gather(self.data, self.idx)
             t += time.perf_counter() - t0
