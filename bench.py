@@ -78,15 +78,17 @@ def measure_link(gv, torch, np):
     torch.cuda.synchronize()
     res["hbm_copy_rw"] = round(2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
     # both directions at once (two streams of default priority): the ceiling for
-    # a fault that writes a dirty victim back while other waves fetch
+    # a fault that writes a dirty victim back while other waves fetch.  256 waves
+    # per direction is where two plain copies peak (48.5 GB/s each way; 45.5 with
+    # 1024 per direction, 39.7 with 2048)
     h2 = gv.pinned_array((nbytes,), np.uint8)
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     best = 0.0
     for _ in range(3):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        gv.gpuvm_bench_copy(d, h, nbytes, 65536, 1024, stream=s1)
-        gv.gpuvm_bench_copy(h2, d2, nbytes, 65536, 1024, stream=s2)
+        gv.gpuvm_bench_copy(d, h, nbytes, 4096, 256, stream=s1)
+        gv.gpuvm_bench_copy(h2, d2, nbytes, 4096, 256, stream=s2)
         torch.cuda.synchronize()
         best = max(best, nbytes / (time.perf_counter() - t0) / 1e9)
     res["duplex_each_direction"] = round(best, 2)
