@@ -170,7 +170,10 @@ GPUVM_API int gpuvm_check(gpuvm_t *vm, void *stream);
 
 /* Largest number of wavefronts a launcher will keep in flight on this handle:
  * each wave holds at most one pinned page plus one frame under migration, so
- * it is min(n_frames / 2, what the device can hold). */
+ * it is min(n_frames / 2, what the device can hold).  Kernels written against
+ * gpuvm_device.h must stay within it too (size the grid from it and stride
+ * over the work); beyond it the bounded waits may end a launch with
+ * GPUVM_EDEADLK. */
 GPUVM_API int gpuvm_max_waves(const gpuvm_t *vm);
 /* The same for the launchers whose faults write back as much as they fetch
  * (gpuvm_run_scatter_increment); see gpuvm_set_waves_per_cu. */

@@ -27,7 +27,10 @@
  * a wave holds at most ONE frame (a pinned page, or the frame it is filling),
  * so frames in use never exceed the number of waves in flight; the launchers
  * keep that below half the frame pool, which is what makes "pass over a
- * pinned frame" always find a victim.
+ * pinned frame" always find a victim.  A kernel of your own has to do the
+ * same: launch no more wavefronts than gpuvm_max_waves() returns for every
+ * handle the kernel touches (grid-stride over the work), and let a wave hold
+ * at most one gpuvm_acquire per handle at a time.
  *
  * Page-table word (one 64-bit atomic per page, all updates are atomics that
  * leave the pin count of concurrent users intact):
