@@ -68,7 +68,7 @@ int main(int argc, char **argv) {
     std::vector<std::vector<u64>> last(threads, std::vector<u64>(priv, 0));
 
     auto body = [&](unsigned t) {
-        blockIdx.x = t;
+        blockIdx.x = t >> 1;                                      // two waves per workgroup share a counter shard
         rng_t r{seed * 1000003ull + t * 7919ull + 1};
         for (unsigned k = 0; k < priv; ++k) last[t][k] = init_val[k * stride + t];
         for (unsigned n = 0; n < ops && failures.load() == 0; ++n) {
