@@ -366,6 +366,29 @@ class BfsWorkload:
     def config(self):
         return {"vertices": self.nv, "edges": int(self.arr.size), "levels": self.levels}
 
+    def baselines(self, oracle):
+        """The same edge-balanced BFS reading col_idx in place in pinned host memory
+        (zero-copy: no page table, no frames), and on a copy of col_idx in HBM."""
+        if type(self) is not BfsWorkload or self.naive:
+            return {}
+        gv, torch, np = self.gv, self.torch, self.np
+        want = oracle.bfs(self._rp, self.arr, 0)
+        res = {}
+
+        def timed(run):
+            ts = []
+            for _ in range(3):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                run()
+                torch.cuda.synchronize()
+                ts.append((time.perf_counter() - t0) * 1e3)
+            return {"best_ms": round(min(ts), 3), "parity": bool(np.array_equal(self.d_level.cpu().numpy(), want))}
+
+        res["zero_copy_pinned_host"] = timed(lambda: gv.gpuvm_bench_bfs_zero_copy(self.vm, self.d_rp, self.nv, 0, self.d_level))
+        res["zero_copy_pinned_host"]["edge_bytes_needed"] = self.useful_bytes
+        return res
+
 
 class CcWorkload(BfsWorkload):
     """Weakly connected components (label propagation, edge-balanced) on the BFS graph."""

@@ -378,6 +378,15 @@ GPUVM_API int gpuvm_bench_read(const void *src, size_t bytes, size_t chunk_bytes
 GPUVM_API int gpuvm_bench_latency(const void *src, size_t bytes, int hops, double *ns_per_hop_out,
                                   void *stream);
 
+/* Zero-copy baseline of gpuvm_run_bfs_balanced: the same edge-balanced kernel
+ * reading col_idx in place in the handle's pinned host buffer, with no page
+ * table and no frames (direct access, the alternative to demand paging on a
+ * GPU whose wavefronts can address host memory).  Same arguments and result;
+ * the handle only names the buffer
+ * and its page geometry, its tables and counters are not touched. */
+GPUVM_API int gpuvm_bench_bfs_zero_copy(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src,
+                                        int32_t *d_level, int *n_levels_out, void *stream);
+
 /* Plain device-resident random gather with no page table (the ceiling for
  * hits): out[k] = data[idx[k]]. */
 GPUVM_API int gpuvm_bench_gather_plain(const uint32_t *d_data, const uint32_t *d_idx,

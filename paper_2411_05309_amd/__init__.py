@@ -89,6 +89,7 @@ _SIGNATURES = {
     "gpuvm_run_stream_reduce": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_bfs": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_bfs_balanced": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
+    "gpuvm_bench_bfs_zero_copy": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_cc_balanced": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_sssp_balanced": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_embedding_bag": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
@@ -260,6 +261,12 @@ def gpuvm_run_stream_reduce(vm, block_elems, d_sums, stream=None):
 def gpuvm_run_bfs(vm, d_row_ptr, nv, src, d_level, stream=None):
     levels = C.c_int(0)
     _call("gpuvm_run_bfs", vm, _ptr(d_row_ptr), nv, src, _ptr(d_level), C.byref(levels), _stream(stream))
+    return levels.value
+
+
+def gpuvm_bench_bfs_zero_copy(vm, d_row_ptr, nv, src, d_level, stream=None):
+    levels = C.c_int(0)
+    _call("gpuvm_bench_bfs_zero_copy", vm, _ptr(d_row_ptr), nv, src, _ptr(d_level), C.byref(levels), _stream(stream))
     return levels.value
 
 

@@ -79,7 +79,9 @@ __global__ void k_bfs_page_owner(const int64_t *__restrict__ row_ptr, int64_t nv
 // Short segments are walked one lane per vertex, long ones by the whole wave.
 // visit(v, u, byte_off, ptr2): edge v -> u stored at byte_off of the page; ptr2
 // is the frame of the same page of a second paged array (edge weights) or null.
-template <class Active, class Visit>
+// DIRECT = true is the zero-copy baseline: the same walk reading col_idx in
+// place in pinned host memory (system-scope loads), no page table, no frames.
+template <bool DIRECT = false, class Active, class Visit>
 __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gpuvm_dev_t *vm2,
                                                  const int64_t *__restrict__ row_ptr,
                                                  const unsigned int *__restrict__ page_owner,
@@ -105,9 +107,13 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
             const int len = end > beg ? (int)(end - beg) : 0;
             if (__builtin_amdgcn_ballot_w64(len > 0) == 0) continue;
             if (!ptr) {
-                ptr = gpuvm_acquire(vm, page, false);
+                ptr = DIRECT ? vm.host + ((size_t)page << vm.page_shift) : gpuvm_acquire(vm, page, false);
                 if (vm2) ptr2 = gpuvm_acquire(*vm2, page, false);
             }
+            auto edge_at = [&](unsigned int o) {
+                return DIRECT ? (int32_t)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(ptr, 1u << vm.page_shift), o, 0, GPUVM_AUX_SYSTEM)
+                              : (int32_t)gpuvm_frame_load_b32(vm, ptr, o);
+            };
             const bool small = len > 0 && len <= kSmall;
             int longest = small ? len : 0;
 #pragma unroll
@@ -116,7 +122,7 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
             for (int j = 0; j < longest; ++j) {
                 if (small && j < len) {
                     const unsigned int o = my_off + ((unsigned int)j << 2);
-                    visit(v, (int32_t)gpuvm_frame_load_b32(vm, ptr, o), o, ptr2);
+                    visit(v, edge_at(o), o, ptr2);
                 }
             }
             unsigned long long todo = __builtin_amdgcn_ballot_w64(len > kSmall);
@@ -128,22 +134,23 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
                 const int64_t vl = vb + l;
                 for (unsigned int i = lane; i < n; i += 64) {
                     const unsigned int o = off0 + (i << 2);
-                    visit(vl, (int32_t)gpuvm_frame_load_b32(vm, ptr, o), o, ptr2);
+                    visit(vl, edge_at(o), o, ptr2);
                 }
             }
         }
-        if (ptr) {
+        if (ptr && !DIRECT) {
             gpuvm_release(vm, page);
             if (vm2) gpuvm_release(*vm2, page);
         }
     }
 }
 
+template <bool DIRECT>
 __global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
                                                                 const unsigned int *__restrict__ page_owner,
                                                                 int32_t *level, int32_t cur, int *changed) {
     int found = 0;
-    walk_owned_pages(vm, nullptr, row_ptr, page_owner,
+    walk_owned_pages<DIRECT>(vm, nullptr, row_ptr, page_owner,
                      [&](int64_t v) { return level[v] == cur; },
                      [&](int64_t, int32_t u, unsigned int, const char *) {
                          if (level[u] < 0) { level[u] = cur + 1; found = 1; }
@@ -206,11 +213,13 @@ extern "C" {
 static int ensure_page_owner(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, hipStream_t s);
 
 static int run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
-                   int *n_levels_out, void *stream, bool balanced) {
+                   int *n_levels_out, void *stream, bool balanced, bool direct = false) {
     if (!vm || !d_row_ptr || !d_level || nv <= 0 || src < 0 || src >= nv || nv > 0x7FFFFFFF) return GPUVM_EINVAL;
     if (vm->dev.bytes % 4) return GPUVM_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    const int waves = launch_waves(vm, balanced ? (size_t)vm->dev.n_pages : (size_t)((nv + 63) / 64));
+    // the zero-copy baseline holds no frames: its waves are bounded by the device only
+    const int waves = direct ? vm->cus * vm->waves_per_cu
+                             : launch_waves(vm, balanced ? (size_t)vm->dev.n_pages : (size_t)((nv + 63) / 64));
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
     if (balanced) {
         int rc0 = ensure_page_owner(vm, d_row_ptr, nv, s);
@@ -222,9 +231,12 @@ static int run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t sr
     for (int32_t cur = 0;; ++cur) {
         int changed = 0;
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
-        if (balanced)
-            k_bfs_level_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, d_level,
-                                                                           cur, vm->bfs_changed);
+        if (direct)
+            k_bfs_level_balanced<true><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner,
+                                                                                 d_level, cur, vm->bfs_changed);
+        else if (balanced)
+            k_bfs_level_balanced<false><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner,
+                                                                                  d_level, cur, vm->bfs_changed);
         else
             k_bfs_level<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, nv, d_level, cur, vm->bfs_changed);
         HIP_TRY(hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -246,6 +258,11 @@ int gpuvm_run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src
 int gpuvm_run_bfs_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
                            int *n_levels_out, void *stream) {
     return run_bfs(vm, d_row_ptr, nv, src, d_level, n_levels_out, stream, true);
+}
+
+int gpuvm_bench_bfs_zero_copy(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src, int32_t *d_level,
+                              int *n_levels_out, void *stream) {
+    return run_bfs(vm, d_row_ptr, nv, src, d_level, n_levels_out, stream, true, true);
 }
 
 static int ensure_page_owner(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, hipStream_t s) {

@@ -355,3 +355,14 @@ def test_vector_add_overwrite_installs_without_fetching(gpu, n, page, frames):
             gv.gpuvm_run_vector_add_overwrite(ba.vm, bb.vm, bc.vm, n - 3 if (n - 3) * 4 % page else n - 5)
         with pytest.raises(gv.GpuvmError):
             gv.gpuvm_run_vector_add_overwrite(ba.vm, bb.vm, ba.vm, n)
+
+
+def test_bfs_zero_copy_baseline_matches_the_oracle(gpu):
+    rp, ci = inputs.rmat_csr(9, 14)
+    want = oracle.bfs(rp, ci, 0)
+    with Backing(ci, 4096, 16 * 4096) as b:
+        d_level = torch.zeros(1 << 14, dtype=torch.int32, device="cuda")
+        levels = gv.gpuvm_bench_bfs_zero_copy(b.vm, dev(rp), 1 << 14, 0, d_level)
+        assert levels >= 2 and np.array_equal(host(d_level, np.int32), want)
+        st = gv.gpuvm_stats(b.vm)
+        assert st["faults"] == 0                                   # nothing was paged
