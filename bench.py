@@ -665,6 +665,13 @@ class EmbeddingWorkload:
                 "G_rows_per_s": round(n / ms / 1e6, 3), "row_GBps": round(n * self.dim * 4 / ms / 1e6, 1), "parity": ok}
         finally:
             gv.gpuvm_destroy(vm2)
+        # zero-copy: the whole job (all batches) with the rows read in place in pinned host memory
+        def all_batches():
+            for bt in range(self.batches):
+                gv.gpuvm_bench_embedding_bag_zero_copy(self.vm, self.dim, self.d_ids[bt], self.bags, self.bag_len, self.d_out[bt])
+        ms = best_ms(all_batches, reps=2)
+        res["zero_copy_pinned_host_whole_job"] = {"best_ms": round(ms, 2), "parity": self.verify(oracle, sample_bags=64),
+                                                  "row_GBps": round(self.useful_bytes / ms / 1e6, 1)}
         dev_rows = torch.from_numpy(sub).cuda()
         long_ids = d_ids.long()
         ms = best_ms(lambda: torch.nn.functional.embedding_bag(long_ids, dev_rows, mode="sum"))

@@ -387,6 +387,12 @@ GPUVM_API int gpuvm_bench_latency(const void *src, size_t bytes, int hops, doubl
 GPUVM_API int gpuvm_bench_bfs_zero_copy(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t src,
                                         int32_t *d_level, int *n_levels_out, void *stream);
 
+/* The same for gpuvm_run_embedding_bag: rows are read in place in the pinned
+ * host buffer, 64 lanes on one contiguous row. */
+GPUVM_API int gpuvm_bench_embedding_bag_zero_copy(gpuvm_t *vm, size_t dim, const int32_t *d_ids,
+                                                  size_t bags, size_t bag_len, float *d_out,
+                                                  void *stream);
+
 /* Plain device-resident random gather with no page table (the ceiling for
  * hits): out[k] = data[idx[k]]. */
 GPUVM_API int gpuvm_bench_gather_plain(const uint32_t *d_data, const uint32_t *d_idx,

@@ -93,6 +93,7 @@ _SIGNATURES = {
     "gpuvm_run_cc_balanced": ([C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_sssp_balanced": ([C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.POINTER(C.c_int), C.c_void_p], C.c_int),
     "gpuvm_run_embedding_bag": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_bench_embedding_bag_zero_copy": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_matvec_t": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_matvec": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_filter_sum": ([C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
@@ -287,6 +288,10 @@ def gpuvm_run_sssp_balanced(vm, vm_weights, d_row_ptr, nv, src, d_dist, stream=N
     _call("gpuvm_run_sssp_balanced", vm, vm_weights, _ptr(d_row_ptr), nv, src, _ptr(d_dist), C.byref(rounds),
           _stream(stream))
     return rounds.value
+
+
+def gpuvm_bench_embedding_bag_zero_copy(vm, dim, d_ids, bags, bag_len, d_out, stream=None):
+    _call("gpuvm_bench_embedding_bag_zero_copy", vm, dim, _ptr(d_ids), bags, bag_len, _ptr(d_out), _stream(stream))
 
 
 def gpuvm_run_embedding_bag(vm, dim, d_ids, bags, bag_len, d_out, stream=None):

@@ -149,7 +149,9 @@ __global__ __launch_bounds__(kBlock) void k_stream_reduce(gpuvm_dev_t vm, unsign
 
 // Embedding bag, sum pooling: one wave per bag; a row of 64*VPL floats is read
 // as VPL consecutive floats per lane; rows are added in listed order in fp32.
-template <int VPL>
+// DIRECT = true is the zero-copy baseline: the rows are read in place in pinned
+// host memory (system-scope loads), no page table, no frames.
+template <int VPL, bool DIRECT = false>
 __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const int32_t *__restrict__ ids,
                                                            size_t bags, unsigned int bag_len, float *__restrict__ out,
                                                            unsigned long long n_rows) {
@@ -161,13 +163,15 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
     constexpr int kRowBatch = 4;
     auto load_row = [&](const char *p, unsigned int o) {
         vec_t r4;
+        constexpr int aux = DIRECT ? GPUVM_AUX_SYSTEM : GPUVM_AUX_AGENT;
+        const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(p, 1u << vm.page_shift);
         if constexpr (VPL == 1) {
-            r4 = __uint_as_float(gpuvm_frame_load_b32(vm, p, o));
+            r4 = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, o, 0, aux));
         } else if constexpr (VPL == 2) {
-            const u32x2 r = gpuvm_frame_load_b64(vm, p, o);
+            const u32x2 r = __builtin_amdgcn_raw_buffer_load_b64(rsrc, o, 0, aux);
             r4.x = __uint_as_float(r.x); r4.y = __uint_as_float(r.y);
         } else {
-            const u32x4 r = gpuvm_frame_load_b128(vm, p, o);
+            const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o, 0, aux);
             r4.x = __uint_as_float(r.x); r4.y = __uint_as_float(r.y);
             r4.z = __uint_as_float(r.z); r4.w = __uint_as_float(r.w);
         }
@@ -198,7 +202,18 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
                     const unsigned long long byte = (live[b] ? id : 0ull) * row_bytes;
                     page[b] = (unsigned int)(byte >> vm.page_shift);
                     o[b] = (unsigned int)(byte & ((1ull << vm.page_shift) - 1)) + lane * (VPL * 4u);
-                    token[b] = gpuvm_peek_begin(vm, page[b]);
+                    token[b] = DIRECT ? 0ull : gpuvm_peek_begin(vm, page[b]);
+                }
+                if constexpr (DIRECT) {
+#pragma unroll
+                    for (int b = 0; b < kRowBatch; ++b) {
+                        v[b] = 0.0f;
+                        if (live[b]) v[b] = load_row(vm.host + ((size_t)page[b] << vm.page_shift), o[b]);
+                    }
+#pragma unroll
+                    for (int b = 0; b < kRowBatch; ++b)
+                        if (live[b]) acc += v[b];
+                    continue;
                 }
 #pragma unroll
                 for (int b = 0; b < kRowBatch; ++b) {
@@ -477,23 +492,41 @@ int gpuvm_run_stream_reduce(gpuvm_t *vm, size_t block_elems, double *d_sums, voi
     return GPUVM_OK;
 }
 
-int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids, size_t bags, size_t bag_len,
-                            float *d_out, void *stream) {
+static int run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids, size_t bags, size_t bag_len,
+                             float *d_out, void *stream, bool direct) {
     if (!vm || !d_ids || !d_out || bag_len == 0 || bag_len > 0xFFFFFFFFu) return GPUVM_EINVAL;
     if (dim != 64 && dim != 128 && dim != 256) return GPUVM_EINVAL;
     const size_t row_bytes = dim * 4;
     if (vm->page_bytes % row_bytes || vm->dev.bytes % row_bytes) return GPUVM_EINVAL;
     if (bags == 0) return GPUVM_OK;
-    const int waves = launch_waves(vm, bags);
+    // the zero-copy baseline holds no frames: its waves are bounded by the device only
+    const int waves = direct ? vm->cus * vm->waves_per_cu : launch_waves(vm, bags);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
     const int grid = grid_for_waves(waves);
     hipStream_t s = (hipStream_t)stream;
     const unsigned long long n_rows = vm->dev.bytes / row_bytes;
-    if (dim == 64) k_embedding_bag<1><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, (unsigned int)bag_len, d_out, n_rows);
-    else if (dim == 128) k_embedding_bag<2><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, (unsigned int)bag_len, d_out, n_rows);
-    else k_embedding_bag<4><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, (unsigned int)bag_len, d_out, n_rows);
+    const unsigned int len = (unsigned int)bag_len;
+    if (direct) {
+        if (dim == 64) k_embedding_bag<1, true><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, len, d_out, n_rows);
+        else if (dim == 128) k_embedding_bag<2, true><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, len, d_out, n_rows);
+        else k_embedding_bag<4, true><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, len, d_out, n_rows);
+    } else {
+        if (dim == 64) k_embedding_bag<1><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, len, d_out, n_rows);
+        else if (dim == 128) k_embedding_bag<2><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, len, d_out, n_rows);
+        else k_embedding_bag<4><<<grid, kBlock, 0, s>>>(vm->dev, d_ids, bags, len, d_out, n_rows);
+    }
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
+}
+
+int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids, size_t bags, size_t bag_len,
+                            float *d_out, void *stream) {
+    return run_embedding_bag(vm, dim, d_ids, bags, bag_len, d_out, stream, false);
+}
+
+int gpuvm_bench_embedding_bag_zero_copy(gpuvm_t *vm, size_t dim, const int32_t *d_ids, size_t bags, size_t bag_len,
+                                        float *d_out, void *stream) {
+    return run_embedding_bag(vm, dim, d_ids, bags, bag_len, d_out, stream, true);
 }
 
 int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, double *d_y, void *stream) {

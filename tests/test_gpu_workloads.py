@@ -366,3 +366,18 @@ def test_bfs_zero_copy_baseline_matches_the_oracle(gpu):
         assert levels >= 2 and np.array_equal(host(d_level, np.int32), want)
         st = gv.gpuvm_stats(b.vm)
         assert st["faults"] == 0                                   # nothing was paged
+
+
+@pytest.mark.parametrize("dim", [64, 128, 256])
+def test_embedding_zero_copy_baseline_matches_the_oracle(gpu, dim):
+    rows, bags, bag_len, page = 3000, 500, 7, 65536
+    rows -= rows % (page // (dim * 4))                              # whole pages of rows
+    table = inputs.f32_uniform(11, 0, rows * dim).reshape(rows, dim)
+    ids = inputs.bag_row_ids(5, 0, bags * bag_len, rows - 1 if np.gcd(2654435761, rows) != 1 else rows, 1.05).reshape(bags, bag_len)
+    ids = np.ascontiguousarray(ids % rows).astype(np.int32)
+    with Backing(table, page, 8 * page) as b:
+        d_out = torch.zeros((bags, dim), dtype=torch.float32, device="cuda")
+        gv.gpuvm_bench_embedding_bag_zero_copy(b.vm, dim, dev(ids), bags, bag_len, d_out)
+        gv.gpuvm_check(b.vm)
+        assert np.array_equal(d_out.cpu().numpy(), oracle.embedding_bag_f32(table, ids))
+        assert gv.gpuvm_stats(b.vm)["faults"] == 0
