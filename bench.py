@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
+    ap.add_argument("--remote-first", type=int, default=0, metavar="BYTES",
+                    help="serve read misses in place until a page has cost its migration; BYTES = what a wavefront reads "
+                         "from a page per access (4 for the gather, 512 for the embedding rows); 0 = the paper's behaviour")
     ap.add_argument("--sweep", default=None, choices=["oversubscription", "page_size", "policy", "writeback"],
                     help="instead of the benchmark line: one JSON line per point of a sweep")
     return ap.parse_args()
@@ -1071,6 +1074,9 @@ def main():
         W.name += "_vertex_chunks"
     if args.waves_per_cu:
         gv.gpuvm_set_waves_per_cu(W.vm, args.waves_per_cu)
+    if args.remote_first:
+        gv.gpuvm_set_remote_first(W.vm, args.remote_first)
+        W.name += f"_remote_first_{args.remote_first}B_per_touch"
 
     def step(events=None):
         gv.gpuvm_reset(W.vm)                         # cold start: all INVALID, frames empty

@@ -81,7 +81,9 @@ typedef struct gpuvm_stats {
     uint64_t phases;            /* barrier phases run by the deterministic launchers    */
     uint64_t faults_no_fetch;   /* of `faults`: pages installed for a full overwrite,
                                    nothing read from the host                           */
-    uint64_t reserved[2];
+    uint64_t remote_reads;      /* page groups served in place over the link instead of
+                                   migrating (gpuvm_set_remote_first)                   */
+    uint64_t reserved[1];
 } gpuvm_stats_t;
 
 /* ---- device-side view: a POD copied by value into kernel arguments -----
@@ -104,6 +106,9 @@ typedef struct gpuvm_dev {
 
 #define GPUVM_F_ACCESS_STATS 1u   /* also count hits / groups / coalesced lanes     */
 #define GPUVM_F_OVERLAPPED_WRITEBACK 2u /* see gpuvm_set_writeback_mode              */
+#define GPUVM_F_REMOTE_SHIFT 8         /* flags >> 8: touches in place before a page
+                                          migrates, 0 = every miss migrates (see
+                                          gpuvm_set_remote_first)                    */
 #define GPUVM_STAT_SLOTS 64
 
 typedef struct gpuvm gpuvm_t;     /* opaque; owned by the library */
@@ -155,6 +160,22 @@ GPUVM_API int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats
  * link in the meantime the measured gain is a few per cent at best. */
 enum { GPUVM_WB_SERIAL = 0, GPUVM_WB_OVERLAPPED = 1 };
 GPUVM_API int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode);
+
+/* Remote-first reads (off by default; not in the paper, whose every miss
+ * migrates the page).  A wavefront of this GPU can read pinned host memory in
+ * place, so a miss has two prices: the bytes of the access itself over the
+ * link, or a whole page.  With bytes_per_touch > 0 a read that misses is
+ * served in place and counted in the page's table word; the page migrates
+ * once those reads have cost as much as the migration would have
+ * (page_bytes / max(bytes_per_touch, 128) touches - the rent-or-buy rule, at
+ * most twice the link traffic of knowing the future).  The count starts again
+ * when the page is evicted.  bytes_per_touch = what one wavefront reads from a
+ * page per access (a 512-byte embedding row, 4 bytes of a gather); 0 turns it
+ * off.  Honoured by the element read accessors (gather, filter, products) and
+ * the embedding launcher; writes and page-level users always migrate; the
+ * deterministic launchers ignore it.  Results do not change, only traffic:
+ * host memory is current for every page that is not resident. */
+GPUVM_API int gpuvm_set_remote_first(gpuvm_t *vm, size_t bytes_per_touch);
 
 /* Wavefronts per compute unit the launchers aim for (1..32, default 8; a
  * launch never uses more wavefronts than half the frames).  Left alone, the

@@ -41,7 +41,9 @@
  *     bits 34..35  state  0 INVALID, 1 LOADING, 2 RESIDENT, 3 EVICTING
  *     bit   36     DEFER  write-aware CLOCK: the hand has spared this dirty page once
  *                         (generalized CLOCK: second bit of the use count)
- *     bits 37..63  frame  valid while RESIDENT / EVICTING
+ *     bits 37..63  frame  valid while RESIDENT / EVICTING; while INVALID: the number
+ *                         of reads served in place since the page was last evicted
+ *                         (remote-first mode, otherwise 0)
  * Frame table: frame_owner[f] = page whose data the frame holds (0xFFFFFFFF
  * before first use).  hand[0] is the global head cursor of the frame ring;
  * ticket t names frame t mod n_frames (paper: Eviction scheme - the leader
@@ -91,7 +93,7 @@ enum {
     GPUVM_S_FAULTS = 0, GPUVM_S_EVICTIONS, GPUVM_S_WB_EVICT, GPUVM_S_WB_FLUSH,
     GPUVM_S_BYTES_IN, GPUVM_S_BYTES_OUT, GPUVM_S_HITS, GPUVM_S_GROUPS,
     GPUVM_S_COALESCED, GPUVM_S_WAITS, GPUVM_S_SKIPS, GPUVM_S_SWEEPS,
-    GPUVM_S_PHASES, GPUVM_S_NOFETCH, GPUVM_S_COUNT = 16
+    GPUVM_S_PHASES, GPUVM_S_NOFETCH, GPUVM_S_REMOTE, GPUVM_S_COUNT = 16
 };
 
 __device__ __forceinline__ bool gpuvm_uses_ref(unsigned int policy) {
@@ -268,6 +270,25 @@ GPUVM_DEV void copy_frame_to_host(char *host, const char *frame, unsigned int by
     wave_copy<GPUVM_AUX_AGENT, GPUVM_AUX_SYSTEM>(host, frame, bytes, w);
 }
 
+/* Remote-first mode: should this read of a page that is not resident be served
+ * in place?  Yes while the page is INVALID and its reads in place have not yet
+ * cost what a migration costs; then the touch is counted (a CAS: the word may
+ * change state under us, and the count shares its bits with the frame index of
+ * a resident page).  No: the caller migrates the page.  One lane calls this. */
+GPUVM_DEV bool touch_in_place(const gpuvm_dev_t &vm, unsigned int page) {
+    const unsigned long long limit = vm.flags >> GPUVM_F_REMOTE_SHIFT;
+    unsigned long long cur = a_load(vm.pte + page);
+    for (int tries = 0; tries < 4; ++tries) {
+        if (((cur & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_INVALID) return false;
+        if ((cur >> GPUVM_PTE_FRAME_SHIFT) + 1 >= limit) return false;
+        if (a_cas(vm.pte + page, &cur, cur + (1ull << GPUVM_PTE_FRAME_SHIFT))) {
+            stat_add(vm, GPUVM_S_REMOTE, 1);
+            return true;
+        }
+    }
+    return false;
+}
+
 /* Frame allocation + eviction + migration for `page`, whose state word this
  * wave has just moved INVALID -> LOADING.  Returns the frame, or GPUVM_NO_PAGE
  * if a bounded wait ran out (error recorded). */
@@ -396,7 +417,8 @@ GPUVM_DEV char *acquire_page(const gpuvm_dev_t &vm, unsigned int page_any, bool 
             const unsigned long long st = (cur & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT;
             if (st == GPUVM_ST_RESIDENT) break;
             if (st == GPUVM_ST_INVALID) {     /* inter-wave arbitration: one wave locks the entry */
-                if (a_cas(pte, &cur, cur | (GPUVM_ST_LOADING << GPUVM_PTE_STATE_SHIFT))) { how = 1; break; }
+                /* (the bits above the state may hold a count of reads in place: it ends here) */
+                if (a_cas(pte, &cur, (cur & GPUVM_PTE_KEEP_MASK) | (GPUVM_ST_LOADING << GPUVM_PTE_STATE_SHIFT))) { how = 1; break; }
                 continue;
             }
             if (spins == 0) stat_add(vm, GPUVM_S_WAITS, 1);
@@ -578,14 +600,31 @@ GPUVM_DEV bool optimistic_read_stands(const gpuvm_dev_t &vm, unsigned int page, 
 /* miss pass: the lanes in `pending` go through gpuvm_acquire one page at a
  * time (all active lanes help to move each page), so that the wave never holds
  * more than one frame while it waits or allocates */
-template <typename T, typename Op>
+struct no_remote {};      /* tag: this access has no in-place form (writes, atomics) */
+template <typename T, typename Op, typename Remote>
 GPUVM_DEV void access_missing(const gpuvm_dev_t &vm, unsigned int page, unsigned int off, bool write, bool pending,
-                              Op op) {
+                              Op op, Remote remote) {
     for (;;) {
         const unsigned long long todo = __builtin_amdgcn_ballot_w64(pending);
         if (todo == 0) break;
         const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
         const unsigned int group_page = __builtin_amdgcn_readlane(page, first);
+        if constexpr (!__is_same(Remote, no_remote)) {
+            /* remote-first: the group's first lane asks whether the page has earned
+             * its migration yet; if not, the lanes read host memory in place */
+            if (vm.flags >> GPUVM_F_REMOTE_SHIFT) {
+                unsigned int in_place = 0;
+                if (__lane_id() == first) in_place = touch_in_place(vm, group_page) ? 1u : 0u;
+                in_place = __builtin_amdgcn_readlane(in_place, first);
+                if (in_place) {
+                    if (pending && page == group_page) {
+                        remote(reinterpret_cast<T *>(vm.host + ((size_t)group_page << vm.page_shift) + off));
+                        pending = false;
+                    }
+                    continue;
+                }
+            }
+        }
         char *frame = gpuvm_acquire(vm, group_page, write);
         if (pending && page == group_page) {
             op(reinterpret_cast<T *>(frame + off));
@@ -620,10 +659,13 @@ GPUVM_DEV void access_missing(const gpuvm_dev_t &vm, unsigned int page, unsigned
  * Miss pass: lanes whose page was not resident (or whose optimistic read did
  * not validate) are grouped by page - one leader, one fault per page and wave -
  * and go through gpuvm_acquire one page at a time, so that a wave never holds
- * more than one frame while it waits or allocates. */
-template <typename T, typename Op>
+ * more than one frame while it waits or allocates.  A read may come with a
+ * second functor, `remote`: in remote-first mode (gpuvm_set_remote_first) it
+ * is called on the element's address in host memory instead, for as long as
+ * the page has not earned its migration. */
+template <typename T, typename Op, typename Remote = gpuvm_detail::no_remote>
 __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned long long elem, bool write, bool want,
-                                             Op op) {
+                                             Op op, Remote remote = Remote{}) {
     using namespace gpuvm_detail;
     const unsigned long long byte = elem * sizeof(T);
     const unsigned int page = (unsigned int)(byte >> vm.page_shift);              /* address split */
@@ -710,7 +752,7 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
             stat_add(vm, GPUVM_S_HITS, n_groups - n_missing);
         }
     }
-    access_missing<T>(vm, page, off, write, want && !resident, op);
+    access_missing<T>(vm, page, off, write, want && !resident, op, remote);
 }
 
 /* Elements are 4 or 8 bytes wide and are read, written and updated with
@@ -721,9 +763,9 @@ template <typename T>
 __device__ __forceinline__ T gpuvm_load_if(const gpuvm_dev_t &vm, unsigned long long elem, bool want) {
     static_assert(sizeof(T) == 4 || sizeof(T) == 8, "gpuvm_load: 4- or 8-byte elements");
     T v{};
-    gpuvm_access<T>(vm, elem, false, want, [&](T *p) {
-        v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    });
+    gpuvm_access<T>(vm, elem, false, want,
+                    [&](T *p) { v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); },
+                    [&](T *p) { v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM); });   /* in place */
     return v;
 }
 template <typename T>

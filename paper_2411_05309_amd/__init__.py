@@ -22,7 +22,7 @@ WB_SERIAL, WB_OVERLAPPED = 0, 1
 STAT_NAMES = ("faults", "evictions", "writebacks_evict", "writebacks_flush",
               "bytes_in", "bytes_out", "hits", "wave_page_groups",
               "lanes_coalesced", "loading_waits", "alloc_skips", "alloc_sweeps",
-              "phases", "faults_no_fetch")
+              "phases", "faults_no_fetch", "remote_reads")
 
 # page-table word layout (include/gpuvm_device.h)
 PTE_PIN_MASK = 0xFFFFF
@@ -45,7 +45,7 @@ class GpuvmError(RuntimeError):
 
 
 class Stats(C.Structure):
-    _fields_ = [(n, C.c_uint64) for n in STAT_NAMES] + [("reserved", C.c_uint64 * 2)]
+    _fields_ = [(n, C.c_uint64) for n in STAT_NAMES] + [("reserved", C.c_uint64 * 1)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n in STAT_NAMES}
@@ -70,6 +70,7 @@ _SIGNATURES = {
     "gpuvm_device_handle": ([C.c_void_p, C.POINTER(Dev)], C.c_int),
     "gpuvm_configure": ([C.c_void_p, C.c_uint32, C.c_int], C.c_int),
     "gpuvm_set_writeback_mode": ([C.c_void_p, C.c_int], C.c_int),
+    "gpuvm_set_remote_first": ([C.c_void_p, C.c_size_t], C.c_int),
     "gpuvm_set_waves_per_cu": ([C.c_void_p, C.c_int], C.c_int),
     "gpuvm_check": ([C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_max_waves": ([C.c_void_p], C.c_int),
@@ -184,6 +185,10 @@ def gpuvm_configure(vm, spin_limit=0, access_stats=False):
 
 def gpuvm_set_writeback_mode(vm, mode):
     _call("gpuvm_set_writeback_mode", vm, mode)
+
+
+def gpuvm_set_remote_first(vm, bytes_per_touch):
+    _call("gpuvm_set_remote_first", vm, bytes_per_touch)
 
 
 def gpuvm_set_waves_per_cu(vm, waves_per_cu):

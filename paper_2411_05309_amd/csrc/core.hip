@@ -192,6 +192,18 @@ int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode) {
     return GPUVM_OK;
 }
 
+int gpuvm_set_remote_first(gpuvm_t *vm, size_t bytes_per_touch) {
+    if (!vm) return GPUVM_EINVAL;
+    uint32_t touches = 0;
+    if (bytes_per_touch) {
+        // rent or buy: migrate once the reads in place have cost one page
+        const size_t per_touch = std::max<size_t>(bytes_per_touch, 128);
+        touches = (uint32_t)std::min<size_t>(std::max<size_t>(vm->page_bytes / per_touch, 2), (1u << 24) - 1);
+    }
+    vm->dev.flags = (vm->dev.flags & ((1u << GPUVM_F_REMOTE_SHIFT) - 1)) | (touches << GPUVM_F_REMOTE_SHIFT);
+    return GPUVM_OK;
+}
+
 int gpuvm_set_waves_per_cu(gpuvm_t *vm, int waves_per_cu) {
     if (!vm || waves_per_cu < 1 || waves_per_cu > 32) return GPUVM_EINVAL;
     vm->waves_per_cu = waves_per_cu;

@@ -161,9 +161,11 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
     const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
     const unsigned int row_bytes = 64u * VPL * 4u;
     constexpr int kRowBatch = 4;
-    auto load_row = [&](const char *p, unsigned int o) {
+    typedef std::integral_constant<bool, DIRECT> from_frame_t;       // frames, unless the whole kernel reads in place
+    typedef std::integral_constant<bool, true> from_host_t;
+    auto load_row = [&](const char *p, unsigned int o, auto in_host) {
         vec_t r4;
-        constexpr int aux = DIRECT ? GPUVM_AUX_SYSTEM : GPUVM_AUX_AGENT;
+        constexpr int aux = decltype(in_host)::value ? GPUVM_AUX_SYSTEM : GPUVM_AUX_AGENT;
         const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(p, 1u << vm.page_shift);
         if constexpr (VPL == 1) {
             r4 = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, o, 0, aux));
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
 #pragma unroll
                     for (int b = 0; b < kRowBatch; ++b) {
                         v[b] = 0.0f;
-                        if (live[b]) v[b] = load_row(vm.host + ((size_t)page[b] << vm.page_shift), o[b]);
+                        if (live[b]) v[b] = load_row(vm.host + ((size_t)page[b] << vm.page_shift), o[b], from_host_t{});
                     }
 #pragma unroll
                     for (int b = 0; b < kRowBatch; ++b)
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
                 for (int b = 0; b < kRowBatch; ++b) {
                     p[b] = live[b] ? gpuvm_token_frame(vm, token[b]) : nullptr;
                     v[b] = 0.0f;
-                    if (p[b]) v[b] = load_row(p[b], o[b]);
+                    if (p[b]) v[b] = load_row(p[b], o[b], from_frame_t{});
                 }
                 gpuvm_wait_reads();
 #pragma unroll
@@ -228,9 +230,18 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
                 for (int b = 0; b < kRowBatch; ++b) {
                     if (!live[b]) continue;
                     if (!(p[b] && gpuvm_peek_same(vm, page[b], token[b], again[b]))) {
-                        const char *q = gpuvm_acquire(vm, page[b], false);
-                        v[b] = load_row(q, o[b]);
-                        gpuvm_release(vm, page[b]);
+                        // remote-first: a page that has not earned its migration yet
+                        // gives up its row in place, 512 bytes over the link
+                        unsigned int in_place = 0;
+                        if ((vm.flags >> GPUVM_F_REMOTE_SHIFT) && lane == 0) in_place = touch_in_place(vm, page[b]) ? 1u : 0u;
+                        if (__builtin_amdgcn_readfirstlane(in_place)) {
+                            v[b] = load_row(vm.host + ((size_t)page[b] << vm.page_shift), o[b], from_host_t{});
+                            gpuvm_wait_reads();
+                        } else {
+                            const char *q = gpuvm_acquire(vm, page[b], false);
+                            v[b] = load_row(q, o[b], from_frame_t{});
+                            gpuvm_release(vm, page[b]);
+                        }
                     }
                     acc += v[b];
                 }

@@ -44,7 +44,7 @@ class Backing:
         self.close()
 
 
-def check_invariants(b, read_only=True, pristine=None):
+def check_invariants(b, read_only=True, pristine=None, remote_first=False):
     """Quiesced-state invariants of the page table / frame table / counters."""
     gv.gpuvm_check(b.vm)
     pte, owner, hand = gv.gpuvm_dump_tables(b.vm)
@@ -59,7 +59,9 @@ def check_invariants(b, read_only=True, pristine=None):
     assert len(np.unique(frames)) == len(res), "two pages share a frame"
     assert np.all(owner[frames] == res), "frame table and page table disagree"
     inv = f["state"] == gv.ST_INVALID
-    assert np.all((pte[inv] & ~np.uint64(gv.PTE_GEN_MASK)) == 0), "stale bits on an INVALID entry"
+    # (in remote-first mode the frame bits of an INVALID entry count its reads in place)
+    keep = np.uint64(gv.PTE_GEN_MASK) | (np.uint64((1 << 64) - (1 << gv.PTE_FRAME_SHIFT)) if remote_first else np.uint64(0))
+    assert np.all((pte[inv] & ~keep) == 0), "stale bits on an INVALID entry"
     # a page's install generation counts its faults (mod 4096)
     if st["faults"] < 4096:                      # no single page can have wrapped
         assert int(f["gen"].sum()) == st["faults"]

@@ -10,7 +10,7 @@
 // and after writing the dirty frames back the host array holds exactly
 // initial value + number of increments, and the last stored values.
 //
-// usage: driver policy threads frames page_bytes pages ops_per_thread seed writeback_mode yield_every
+// usage: driver policy threads frames page_bytes pages ops_per_thread seed writeback_mode yield_every remote_touches
 #include "shim.h"
 #include GPUVM_DEVICE_HEADER
 
@@ -37,12 +37,13 @@ struct rng_t {
 };
 
 int main(int argc, char **argv) {
-    if (argc != 10) { fprintf(stderr, "usage: see the head of driver.cpp\n"); return 2; }
+    if (argc != 11) { fprintf(stderr, "usage: see the head of driver.cpp\n"); return 2; }
     const unsigned policy = atoi(argv[1]), threads = atoi(argv[2]), frames = atoi(argv[3]);
     const unsigned page_bytes = atoi(argv[4]), pages = atoi(argv[5]), ops = atoi(argv[6]);
     const u64 seed = strtoull(argv[7], nullptr, 10);
     const unsigned wb_mode = atoi(argv[8]);
     shim_yield_every = atoi(argv[9]);
+    const unsigned remote_touches = atoi(argv[10]);         // 0: every miss migrates; else reads in place before migration
     if (frames < 2 * threads || frames < 8) { fprintf(stderr, "need frames >= max(8, 2 * threads)\n"); return 2; }
 
     const u64 per_page = page_bytes / 8;
@@ -60,7 +61,7 @@ int main(int argc, char **argv) {
     vm.pte = pte.data(); vm.frame_owner = owner.data(); vm.hand = hand.data(); vm.stats = stats.data();
     vm.frames = pool.data(); vm.host = (char *)host.data();
     vm.bytes = n_shared * 8; vm.n_pages = pages; vm.n_frames = frames; vm.page_shift = shift;
-    vm.policy = policy; vm.spin_limit = 1u << 30; vm.flags = wb_mode ? GPUVM_F_OVERLAPPED_WRITEBACK : 0;
+    vm.policy = policy; vm.spin_limit = 1u << 30; vm.flags = (wb_mode ? GPUVM_F_OVERLAPPED_WRITEBACK : 0) | (remote_touches << GPUVM_F_REMOTE_SHIFT);
 
     // element i is private to thread t if i % stride == t (t < threads) and i / stride < priv
     const u64 stride = n_shared / priv;
@@ -136,7 +137,9 @@ int main(int argc, char **argv) {
         const unsigned st = (unsigned)((w & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT);
         if (w & GPUVM_PTE_PIN_MASK) fail("reference count left", p, w, 0);
         if (st == GPUVM_ST_INVALID) {
-            if (w & ~(u64)GPUVM_PTE_GEN_MASK) fail("stale bits on an INVALID entry", p, w, 0);
+            const u64 touch_bits = remote_touches ? ~0ull << GPUVM_PTE_FRAME_SHIFT : 0ull;   // count of reads in place
+            if (w & ~((u64)GPUVM_PTE_GEN_MASK | touch_bits)) fail("stale bits on an INVALID entry", p, w, 0);
+            if (remote_touches && (w >> GPUVM_PTE_FRAME_SHIFT) >= remote_touches) fail("more reads in place than a migration costs", p, w, remote_touches);
         } else if (st == GPUVM_ST_RESIDENT) {
             const unsigned f = (unsigned)(w >> GPUVM_PTE_FRAME_SHIFT);
             if (f >= frames || owner[f] != p || seen[f]++) fail("page table and frame table disagree", p, f, f < frames ? owner[f] : 0);
@@ -162,8 +165,9 @@ int main(int argc, char **argv) {
         incs += completed[i].load();
     }
     printf("{\"failures\": %d, \"faults\": %llu, \"evictions\": %llu, \"writebacks_evict\": %llu, \"loading_waits\": %llu, "
-           "\"alloc_skips\": %llu, \"alloc_sweeps\": %llu, \"resident\": %llu, \"dirty_at_end\": %llu, \"increments\": %llu}\n",
+           "\"alloc_skips\": %llu, \"alloc_sweeps\": %llu, \"resident\": %llu, \"dirty_at_end\": %llu, \"increments\": %llu, "
+           "\"remote_reads\": %llu}\n",
            failures.load(), tot[GPUVM_S_FAULTS], tot[GPUVM_S_EVICTIONS], tot[GPUVM_S_WB_EVICT], tot[GPUVM_S_WAITS],
-           tot[GPUVM_S_SKIPS], tot[GPUVM_S_SWEEPS], resident, dirty, incs);
+           tot[GPUVM_S_SKIPS], tot[GPUVM_S_SWEEPS], resident, dirty, incs, tot[GPUVM_S_REMOTE]);
     return failures.load() ? 1 : 0;
 }

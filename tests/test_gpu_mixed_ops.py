@@ -18,18 +18,19 @@ from gpu_util import Backing, check_invariants, dev, host
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("wb_mode", [gv.WB_SERIAL, gv.WB_OVERLAPPED])
+@pytest.mark.parametrize("wb_mode,remote_bytes", [(gv.WB_SERIAL, 0), (gv.WB_OVERLAPPED, 0), (gv.WB_SERIAL, 4), (gv.WB_SERIAL, 1024)])
 @pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_FIFO_WAIT, gv.POLICY_CLOCK_WRITE_AWARE, gv.POLICY_GCLOCK])
 @pytest.mark.parametrize("n64,page,frames,seed", [
     ((1 << 16) + 37, 4096, 24, 1),       # 129 pages (the last one short) over 24 frames
     (1 << 17, 65536, 8, 2),              # 16 pages of 64 KiB over the smallest pool
 ])
-def test_random_operation_sequence_matches_the_model(gpu, policy, wb_mode, n64, page, frames, seed):
+def test_random_operation_sequence_matches_the_model(gpu, policy, wb_mode, remote_bytes, n64, page, frames, seed):
     model = inputs.u32_values(seed, 0, 2 * n64).view(np.uint64).copy()      # arbitrary initial content
     n_pages = -(-model.nbytes // page)
     pick = inputs.u32_indices(100 + seed, 0, 64, 1 << 16)                   # the op sequence, seeded
     with Backing(model, page, frames * page, policy) as b:
         gv.gpuvm_set_writeback_mode(b.vm, wb_mode)
+        gv.gpuvm_set_remote_first(b.vm, remote_bytes)           # reads that miss may be served in place
         dirty_since_flush = False
         for step, r in enumerate(pick):
             op = int(r) % 8
@@ -58,9 +59,10 @@ def test_random_operation_sequence_matches_the_model(gpu, policy, wb_mode, n64, 
                 assert np.array_equal(b.arr, model), (step, "host array after flush")
                 dirty_since_flush = False
             if step % 8 == 7:
-                st, f, *_ = check_invariants(b, read_only=False)
+                st, f, *_ = check_invariants(b, read_only=False, remote_first=remote_bytes > 0)
                 if not dirty_since_flush:
                     assert not np.any(f["dirty"])
         gv.gpuvm_flush(b.vm)
-        check_invariants(b, read_only=False)
+        st, *_ = check_invariants(b, read_only=False, remote_first=remote_bytes > 0)
+        assert (st["remote_reads"] > 0) == (remote_bytes > 0)
         assert np.array_equal(b.arr, model)
