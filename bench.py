@@ -1075,7 +1075,9 @@ def main():
     if args.waves_per_cu:
         gv.gpuvm_set_waves_per_cu(W.vm, args.waves_per_cu)
     if args.remote_first:
-        gv.gpuvm_set_remote_first(W.vm, args.remote_first)
+        for vm in (W.vm, getattr(W, "vmw", None)):            # second paged array: the filter's value column
+            if vm is not None:
+                gv.gpuvm_set_remote_first(vm, args.remote_first)
         W.name += f"_remote_first_{args.remote_first}B_per_touch"
 
     def step(events=None):
