@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--remote-first", type=int, default=0, metavar="BYTES",
                     help="serve read misses in place until a page has cost its migration; BYTES = what a wavefront reads "
                          "from a page per access (4 for the gather, 512 for the embedding rows); 0 = the paper's behaviour")
-    ap.add_argument("--sweep", default=None, choices=["oversubscription", "page_size", "policy", "writeback"],
+    ap.add_argument("--sweep", default=None, choices=["oversubscription", "page_size", "policy", "writeback", "remote_first"],
                     help="instead of the benchmark line: one JSON line per point of a sweep")
     return ap.parse_args()
 
@@ -1035,6 +1035,47 @@ def sweep_writeback(gv, torch, np, inputs, oracle):
         del d_idx
 
 
+def sweep_remote_first(gv, torch, np, inputs, oracle):
+    """How many reads in place before a page migrates?  The rule in
+    gpuvm_set_remote_first charges a page for its reads in place and migrates it
+    when they have cost one page (rent or buy).  Swept here: the price per read,
+    i.e. the number of touches before migration, on the embedding bag (64 KiB
+    pages, 512-byte rows: the rule gives 128) and the random gather (4 KiB pages:
+    32), from 'migrate at the second touch' to 'never'.  Cold start per point."""
+    for cls, points in (("GatherWorkload", (2048, 1024, 512, 256, 128)), ("EmbeddingWorkload", (32768, 8192, 2048, 512, 128))):
+        W = globals()[cls](gv, torch, np, inputs, gv.POLICY_CLOCK)
+        page = W.page
+        for per_touch in (0,) + points + (-1,):
+            gv.gpuvm_reset(W.vm)
+            if per_touch >= 0:
+                gv.gpuvm_set_remote_first(W.vm, per_touch)
+                touches = page // max(per_touch, 128) if per_touch else 0
+            else:
+                # 'never migrate' is the zero-copy kernel of the same workload
+                gv.gpuvm_set_remote_first(W.vm, 0)
+                base = W.baselines(oracle) if hasattr(W, "baselines") else {}
+                zc = base.get("zero_copy_pinned_host_whole_job") or base.get("zero_copy_pinned_host")
+                print(json.dumps({"sweep": "remote_first", "workload": W.name, "touches_before_migration": "never (zero-copy kernel)",
+                                  "ms": zc.get("best_ms"), "parity": zc.get("parity")}), flush=True)
+                continue
+            torch.cuda.synchronize()
+            e0, e1 = ev_pair(torch)
+            e0.record()
+            W.launch()
+            e1.record()
+            torch.cuda.synchronize()
+            gv.gpuvm_check(W.vm)
+            st = gv.gpuvm_stats(W.vm)
+            print(json.dumps({"sweep": "remote_first", "workload": W.name,
+                              "touches_before_migration": touches if per_touch else "0 (every miss migrates)",
+                              "ms": round(e0.elapsed_time(e1), 2), "pages_migrated": st["faults"], "read_in_place": st["remote_reads"],
+                              "link_GB_pages": round(st["bytes_in"] / 1e9, 3), "parity": bool(W.verify(oracle))}), flush=True)
+        gv.gpuvm_destroy(W.vm)
+        gv.free_pinned(W.arr)
+        del W
+        torch.cuda.empty_cache()
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -1054,7 +1095,7 @@ def main():
     if args.sweep:
         import oracle
         {"oversubscription": sweep_oversubscription, "page_size": sweep_page_size,
-         "policy": sweep_policy, "writeback": sweep_writeback}[args.sweep](gv, torch, np, inputs, oracle)
+         "policy": sweep_policy, "writeback": sweep_writeback, "remote_first": sweep_remote_first}[args.sweep](gv, torch, np, inputs, oracle)
         return
     link = measure_link(gv, torch, np)
     link_peak = max(link["wave_read_4k"], link["wave_read_64k"], link["wave_copy_4k"], link["hipMemcpy_h2d"])
