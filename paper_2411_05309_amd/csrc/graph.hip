@@ -81,6 +81,13 @@ __global__ void k_bfs_page_owner(const int64_t *__restrict__ row_ptr, int64_t nv
 // is the frame of the same page of a second paged array (edge weights) or null.
 // DIRECT = true is the zero-copy baseline: the same walk reading col_idx in
 // place in pinned host memory (system-scope loads), no page table, no frames.
+// In remote-first mode (gpuvm_set_remote_first on the handle, one paged array)
+// the choice is made page by page: a page that is not resident and whose
+// active segments would cost less over the link read in place (64 bytes per
+// short list at least, 4 bytes per edge, times two for the low rate of
+// scattered reads) than the page itself is read in place; everything else is
+// paged in as usual.  The sparse levels of a BFS,
+// where a 64 KiB page is wanted for a handful of edges, are the case.
 template <bool DIRECT = false, class Active, class Visit>
 __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gpuvm_dev_t *vm2,
                                                  const int64_t *__restrict__ row_ptr,
@@ -92,11 +99,33 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
     const unsigned int elems_shift = vm.page_shift - 2;
     const int64_t n_edges = (int64_t)(vm.bytes >> 2);
     constexpr int kSmall = 32;                    // lists up to this length: one lane each
+    // scattered short reads in place run well below the link's bulk rate; on the
+    // scale-26 BFS a factor of 2 was the fastest of 1, 1.5, 2, 3, 4, 8
+    // (206, 146, 139, 142, 146, 157 ms; 197 ms with every page migrated)
+    constexpr unsigned long long kInPlacePenalty = 2;
     for (unsigned int page = wave; page < vm.n_pages; page += nwaves) {
         const int64_t e_lo = (int64_t)page << elems_shift;
         const int64_t e_hi = min((long long)n_edges, (long long)(e_lo + ((int64_t)1 << elems_shift)));
         const int64_t v_first = page_owner[page], v_last = page_owner[page + 1];
         const char *ptr = nullptr, *ptr2 = nullptr;
+        bool in_place = DIRECT;
+        if (!DIRECT && !vm2 && (vm.flags >> GPUVM_F_REMOTE_SHIFT) &&
+            ((a_load(vm.pte + page) & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT) {
+            // what would the active segments of this page cost if read in place?
+            unsigned long long cost = 0;
+            for (int64_t vb = v_first; vb <= v_last && cost * kInPlacePenalty < (1ull << vm.page_shift); vb += 64) {
+                const int64_t v = vb + lane;
+                long long len = 0;
+                if (v <= v_last && active(v))
+                    len = min((long long)row_ptr[v + 1], (long long)e_hi) - max((long long)row_ptr[v], (long long)e_lo);
+                unsigned long long c = len > 0 ? max(64ull, (unsigned long long)len * 4ull) : 0ull;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
+                cost += c;
+            }
+            in_place = cost * kInPlacePenalty < (1ull << vm.page_shift);
+            if (in_place && cost && lane == 0) stat_add(vm, GPUVM_S_REMOTE, 1);
+        }
         for (int64_t vb = v_first; vb <= v_last; vb += 64) {
             const int64_t v = vb + lane;
             int64_t beg = 0, end = 0;
@@ -107,12 +136,12 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
             const int len = end > beg ? (int)(end - beg) : 0;
             if (__builtin_amdgcn_ballot_w64(len > 0) == 0) continue;
             if (!ptr) {
-                ptr = DIRECT ? vm.host + ((size_t)page << vm.page_shift) : gpuvm_acquire(vm, page, false);
+                ptr = in_place ? vm.host + ((size_t)page << vm.page_shift) : gpuvm_acquire(vm, page, false);
                 if (vm2) ptr2 = gpuvm_acquire(*vm2, page, false);
             }
             auto edge_at = [&](unsigned int o) {
-                return DIRECT ? (int32_t)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(ptr, 1u << vm.page_shift), o, 0, GPUVM_AUX_SYSTEM)
-                              : (int32_t)gpuvm_frame_load_b32(vm, ptr, o);
+                return in_place ? (int32_t)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(ptr, 1u << vm.page_shift), o, 0, GPUVM_AUX_SYSTEM)
+                                : (int32_t)gpuvm_frame_load_b32(vm, ptr, o);
             };
             const bool small = len > 0 && len <= kSmall;
             int longest = small ? len : 0;
@@ -138,7 +167,7 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
                 }
             }
         }
-        if (ptr && !DIRECT) {
+        if (ptr && !in_place) {
             gpuvm_release(vm, page);
             if (vm2) gpuvm_release(*vm2, page);
         }

@@ -107,3 +107,29 @@ def test_embedding_bag_results_do_not_change(gpu, dim):
         assert np.array_equal(d_out.cpu().numpy(), want)                      # bit-exact, as before
         st, *_ = check_invariants(b, read_only=True, pristine=table, remote_first=True)
         assert st["remote_reads"] > 0 and st["faults"] < plain["faults"]
+
+
+@pytest.mark.parametrize("scale,page,frames,src", [(14, 4096, 16, 0), (16, 65536, 8, 5), (13, 4096, 8, 77)])
+def test_bfs_reads_sparse_pages_in_place(gpu, scale, page, frames, src):
+    rp, ci = inputs.rmat_csr(9, scale)
+    nv = 1 << scale
+    want = oracle.bfs(rp, ci, src)
+    with Backing(ci, page, frames * page) as b:
+        d_level = torch.zeros(nv, dtype=torch.int32, device="cuda")
+        gv.gpuvm_run_bfs_balanced(b.vm, dev(rp), nv, src, d_level)
+        gv.gpuvm_check(b.vm)
+        plain = gv.gpuvm_stats(b.vm)
+        assert np.array_equal(host(d_level, np.int32), want)
+        gv.gpuvm_reset(b.vm)
+        gv.gpuvm_set_remote_first(b.vm, 4)
+        d_level.zero_()
+        levels = gv.gpuvm_run_bfs_balanced(b.vm, dev(rp), nv, src, d_level)
+        gv.gpuvm_check(b.vm)
+        assert levels >= 2 and np.array_equal(host(d_level, np.int32), want)
+        st, *_ = check_invariants(b, read_only=True, pristine=ci, remote_first=True)
+        assert st["remote_reads"] > 0 and st["faults"] <= plain["faults"]
+        # connected components walk every edge in every round: nothing is sparse, results as before
+        d_label = torch.zeros(nv, dtype=torch.int32, device="cuda")
+        gv.gpuvm_run_cc_balanced(b.vm, dev(rp), nv, d_label)
+        gv.gpuvm_check(b.vm)
+        assert np.array_equal(host(d_label, np.int32), oracle.cc(rp, ci))
