@@ -747,6 +747,21 @@ class ScatterWorkload:
     def config(self):
         return {"elements": self.n_elems, "updates": self.n_upd}
 
+    def baselines(self, oracle):
+        """Zero-copy form of the same job: every update a system-scope atomic executed
+        in place in pinned host memory (no page table).  Adds one more round to the
+        host array, which the check accounts for."""
+        gv, torch = self.gv, self.torch
+        gv.gpuvm_reset(self.vm)                       # the handle steps aside: host memory is all there is
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        gv.gpuvm_bench_scatter_plain(self.arr, self.d_idx, self.n_upd)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3
+        self.rounds += 1
+        return {"zero_copy_pinned_host_atomics": {"ms": round(ms, 1), "M_updates_per_s": round(self.n_upd / ms / 1e3, 2),
+                                                  "parity": self.verify(oracle)}}
+
 
 WORKLOADS = {"gather": GatherWorkload, "stream": StreamWorkload, "bfs": BfsWorkload, "cc": CcWorkload, "sssp": SsspWorkload,
              "matvec_t": MatvecTWorkload, "matvec": MatvecWorkload, "filter": FilterWorkload, "vector_add": VectorAddWorkload, "vector_add_overwrite": VectorAddOverwriteWorkload,

@@ -422,6 +422,13 @@ GPUVM_API int gpuvm_bench_embedding_bag_zero_copy(gpuvm_t *vm, size_t dim, const
 GPUVM_API int gpuvm_bench_gather_plain(const uint32_t *d_data, const uint32_t *d_idx,
                                        size_t n, uint32_t *d_out, void *stream);
 
+/* Plain scatter-increment with no page table: data[idx[k]] += 1 on a uint64
+ * array, with system-scope atomics.  `data` in device memory: the ceiling for
+ * hits of the scatter workload; `data` in pinned host memory: its zero-copy
+ * form, every update an atomic executed over the link.  idx values must be
+ * below the array's length (not checked). */
+GPUVM_API int gpuvm_bench_scatter_plain(uint64_t *data, const uint32_t *d_idx, size_t n, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

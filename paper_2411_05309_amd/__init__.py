@@ -104,6 +104,7 @@ _SIGNATURES = {
     "gpuvm_bench_copy": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p], C.c_int),
     "gpuvm_bench_read": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_bench_latency": ([C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.c_void_p], C.c_int),
+    "gpuvm_bench_scatter_plain": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_bench_gather_plain": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
 }
 
@@ -339,6 +340,10 @@ def gpuvm_bench_latency(src, nbytes, hops=2000, stream=None):
     ns = C.c_double(0.0)
     _call("gpuvm_bench_latency", _ptr(src), nbytes, hops, C.byref(ns), _stream(stream))
     return ns.value
+
+
+def gpuvm_bench_scatter_plain(data, d_idx, n, stream=None):
+    _call("gpuvm_bench_scatter_plain", _ptr(data), _ptr(d_idx), n, _stream(stream))
 
 
 def gpuvm_bench_gather_plain(d_data, d_idx, n, d_out, stream=None):

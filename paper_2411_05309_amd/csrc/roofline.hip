@@ -69,6 +69,16 @@ __global__ __launch_bounds__(kBlock) void k_bench_gather_plain(const uint32_t *_
     for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n; k += nthreads) out[k] = data[idx[k]];
 }
 
+// data[idx[k]] += 1 on a plain uint64 array with no page table: in HBM the
+// ceiling for scatter hits, in pinned host memory (system-scope atomics
+// executed over the link) the zero-copy form of the scatter-increment.
+__global__ __launch_bounds__(kBlock) void k_bench_scatter_plain(unsigned long long *data, const uint32_t *__restrict__ idx,
+                                                                 size_t n) {
+    const size_t nthreads = (size_t)gridDim.x * kBlock;
+    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n; k += nthreads)
+        __hip_atomic_fetch_add(data + idx[k], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 extern "C" {
 
 static int bench_waves(int waves) {
@@ -121,6 +131,15 @@ int gpuvm_bench_gather_plain(const uint32_t *d_data, const uint32_t *d_idx, size
     if (n == 0) return GPUVM_OK;
     const int grid = (int)std::min<size_t>((n + kBlock - 1) / kBlock, 256 * 32);
     k_bench_gather_plain<<<grid, kBlock, 0, (hipStream_t)stream>>>(d_data, d_idx, n, d_out);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_bench_scatter_plain(uint64_t *data, const uint32_t *d_idx, size_t n, void *stream) {
+    if (!data || !d_idx) return GPUVM_EINVAL;
+    if (n == 0) return GPUVM_OK;
+    const int grid = (int)std::min<size_t>((n + kBlock - 1) / kBlock, 256 * 32);
+    k_bench_scatter_plain<<<grid, kBlock, 0, (hipStream_t)stream>>>((unsigned long long *)data, d_idx, n);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }

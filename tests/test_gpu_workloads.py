@@ -381,3 +381,22 @@ def test_embedding_zero_copy_baseline_matches_the_oracle(gpu, dim):
         gv.gpuvm_check(b.vm)
         assert np.array_equal(d_out.cpu().numpy(), oracle.embedding_bag_f32(table, ids))
         assert gv.gpuvm_stats(b.vm)["faults"] == 0
+
+
+def test_plain_scatter_microbenchmark_in_hbm_and_in_host_memory(gpu):
+    n64, n = 1 << 16, 50000
+    idx = inputs.scatter_indices(3, 0, n, n64)
+    want = np.zeros(n64, np.uint64)
+    oracle.scatter_increment(want, idx)
+    d = torch.zeros(n64, dtype=torch.int64, device="cuda")
+    gv.gpuvm_bench_scatter_plain(d, dev(idx), n)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(d, np.uint64), want)
+    h = gv.pinned_array((n64,), np.uint64)
+    try:
+        h[:] = 0
+        gv.gpuvm_bench_scatter_plain(h, dev(idx), n)                  # atomics executed over the link
+        torch.cuda.synchronize()
+        assert np.array_equal(h, want)
+    finally:
+        gv.free_pinned(h)
