@@ -172,8 +172,8 @@ GPUVM_API int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode);
  * when the page is evicted.  bytes_per_touch = what one wavefront reads from a
  * page per access (a 512-byte embedding row, 4 bytes of a gather); 0 turns it
  * off.  Honoured by the element read accessors (gather, filter, products) and
- * the embedding launcher; the edge-balanced graph launchers (one paged array:
- * BFS, CC) use the same trade page by page without a count - a page whose
+ * the embedding launcher; the edge-balanced graph launchers (BFS, CC, SSSP; set
+ * it on the handle of col_idx) use the same trade page by page without a count - a page whose
  * active edge lists would cost less read in place than the page itself is read
  * in place, whatever bytes_per_touch > 0 was given; writes and other page-level
  * users always migrate; the deterministic launchers ignore it.  Results do not change, only traffic:

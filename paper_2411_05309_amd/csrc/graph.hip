@@ -77,12 +77,13 @@ __global__ void k_bfs_page_owner(const int64_t *__restrict__ row_ptr, int64_t nv
 // pages w, w + nwaves, ... of the paged col_idx array for this round; inside a
 // page it visits the edge segments of the vertices for which active(v) holds.
 // Short segments are walked one lane per vertex, long ones by the whole wave.
-// visit(v, u, byte_off, ptr2): edge v -> u stored at byte_off of the page; ptr2
-// is the frame of the same page of a second paged array (edge weights) or null.
+// visit(v, u, byte_off, ptr2, in_place): edge v -> u stored at byte_off of the
+// page; ptr2 is the same page of a second paged array (edge weights) or null - a
+// frame, or host memory if in_place.
 // DIRECT = true is the zero-copy baseline: the same walk reading col_idx in
 // place in pinned host memory (system-scope loads), no page table, no frames.
-// In remote-first mode (gpuvm_set_remote_first on the handle, one paged array)
-// the choice is made page by page: a page that is not resident and whose
+// In remote-first mode (gpuvm_set_remote_first on the handle of col_idx) the
+// choice is made page by page, for both arrays together: a page that is not resident and whose
 // active segments would cost less over the link read in place (64 bytes per
 // short list at least, 4 bytes per edge, times two for the low rate of
 // scattered reads) than the page itself is read in place; everything else is
@@ -109,7 +110,7 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
         const int64_t v_first = page_owner[page], v_last = page_owner[page + 1];
         const char *ptr = nullptr, *ptr2 = nullptr;
         bool in_place = DIRECT;
-        if (!DIRECT && !vm2 && (vm.flags >> GPUVM_F_REMOTE_SHIFT) &&
+        if (!DIRECT && (vm.flags >> GPUVM_F_REMOTE_SHIFT) &&
             ((a_load(vm.pte + page) & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT) {
             // what would the active segments of this page cost if read in place?
             unsigned long long cost = 0;
@@ -118,7 +119,7 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
                 long long len = 0;
                 if (v <= v_last && active(v))
                     len = min((long long)row_ptr[v + 1], (long long)e_hi) - max((long long)row_ptr[v], (long long)e_lo);
-                unsigned long long c = len > 0 ? max(64ull, (unsigned long long)len * 4ull) : 0ull;
+                unsigned long long c = len > 0 ? max(64ull, (unsigned long long)len * 4ull) : 0ull;   // per array: the page count cancels
 #pragma unroll
                 for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
                 cost += c;
@@ -137,7 +138,7 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
             if (__builtin_amdgcn_ballot_w64(len > 0) == 0) continue;
             if (!ptr) {
                 ptr = in_place ? vm.host + ((size_t)page << vm.page_shift) : gpuvm_acquire(vm, page, false);
-                if (vm2) ptr2 = gpuvm_acquire(*vm2, page, false);
+                if (vm2) ptr2 = in_place ? vm2->host + ((size_t)page << vm2->page_shift) : gpuvm_acquire(*vm2, page, false);
             }
             auto edge_at = [&](unsigned int o) {
                 return in_place ? (int32_t)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(ptr, 1u << vm.page_shift), o, 0, GPUVM_AUX_SYSTEM)
@@ -151,7 +152,7 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
             for (int j = 0; j < longest; ++j) {
                 if (small && j < len) {
                     const unsigned int o = my_off + ((unsigned int)j << 2);
-                    visit(v, edge_at(o), o, ptr2);
+                    visit(v, edge_at(o), o, ptr2, in_place);
                 }
             }
             unsigned long long todo = __builtin_amdgcn_ballot_w64(len > kSmall);
@@ -163,7 +164,7 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
                 const int64_t vl = vb + l;
                 for (unsigned int i = lane; i < n; i += 64) {
                     const unsigned int o = off0 + (i << 2);
-                    visit(vl, edge_at(o), o, ptr2);
+                    visit(vl, edge_at(o), o, ptr2, in_place);
                 }
             }
         }
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, c
     int found = 0;
     walk_owned_pages<DIRECT>(vm, nullptr, row_ptr, page_owner,
                      [&](int64_t v) { return level[v] == cur; },
-                     [&](int64_t, int32_t u, unsigned int, const char *) {
+                     [&](int64_t, int32_t u, unsigned int, const char *, bool) {
                          if (level[u] < 0) { level[u] = cur + 1; found = 1; }
                      });
     if (__builtin_amdgcn_ballot_w64(found != 0) && (threadIdx.x & 63) == 0) *changed = 1;
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(kBlock) void k_cc_round_balanced(gpuvm_dev_t vm, co
     int found = 0;
     walk_owned_pages(vm, nullptr, row_ptr, page_owner,
                      [&](int64_t) { return true; },
-                     [&](int64_t v, int32_t u, unsigned int, const char *) {
+                     [&](int64_t v, int32_t u, unsigned int, const char *, bool) {
                          const int32_t lv = __hip_atomic_load(label + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                          const int32_t lu = __hip_atomic_load(label + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                          if (lv < lu) {
@@ -221,8 +222,9 @@ __global__ __launch_bounds__(kBlock) void k_sssp_round_balanced(gpuvm_dev_t vm, 
     int found = 0;
     walk_owned_pages(vm, &vmw, row_ptr, page_owner,
                      [&](int64_t v) { return act_cur[v] != 0; },
-                     [&](int64_t v, int32_t u, unsigned int off, const char *pw) {
-                         const uint32_t w = gpuvm_frame_load_b32(vmw, pw, off);
+                     [&](int64_t v, int32_t u, unsigned int off, const char *pw, bool in_place) {
+                         const uint32_t w = in_place ? __builtin_amdgcn_raw_buffer_load_b32(make_rsrc(pw, 1u << vmw.page_shift), off, 0, GPUVM_AUX_SYSTEM)
+                                                     : gpuvm_frame_load_b32(vmw, pw, off);
                          const uint32_t dv = __hip_atomic_load(dist + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                          if (dv != 0xFFFFFFFFu) {
                              const uint32_t nd = dv + w;

@@ -133,3 +133,19 @@ def test_bfs_reads_sparse_pages_in_place(gpu, scale, page, frames, src):
         gv.gpuvm_run_cc_balanced(b.vm, dev(rp), nv, d_label)
         gv.gpuvm_check(b.vm)
         assert np.array_equal(host(d_label, np.int32), oracle.cc(rp, ci))
+
+
+@pytest.mark.parametrize("scale,page,frames,src", [(14, 4096, 16, 0), (16, 65536, 8, 5)])
+def test_sssp_reads_sparse_pages_of_both_arrays_in_place(gpu, scale, page, frames, src):
+    rp, ci = inputs.rmat_csr(9, scale)
+    w = inputs.edge_weights(4, 0, ci.size)
+    nv = 1 << scale
+    want = oracle.sssp(rp, ci, w, src)
+    with Backing(ci, page, frames * page) as b, Backing(w, page, frames * page) as bw:
+        gv.gpuvm_set_remote_first(b.vm, 4)
+        d_dist = torch.zeros(nv, dtype=torch.int32, device="cuda")
+        rounds = gv.gpuvm_run_sssp_balanced(b.vm, bw.vm, dev(rp), nv, src, d_dist)
+        assert rounds >= 2 and np.array_equal(host(d_dist, np.uint32), want)
+        st, *_ = check_invariants(b, read_only=True, pristine=ci, remote_first=True)
+        check_invariants(bw, read_only=True, pristine=w)
+        assert st["remote_reads"] > 0
