@@ -796,11 +796,14 @@ def sweep_oversubscription(gv, torch, np, inputs, oracle):
     arr[...] = data
     d_idx = torch.from_numpy(idx.view(np.int32)).cuda()
     d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
-    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO), ("fifo_wait", gv.POLICY_FIFO_WAIT)):
+    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO), ("fifo_wait", gv.POLICY_FIFO_WAIT),
+                          ("clock_remote_first", gv.POLICY_CLOCK)):
         base = None
         for lv in levels:
             pool = int(arr.nbytes / (lv + 1)) // page * page
             vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, pool, pol)
+            if pol_name.endswith("remote_first"):
+                gv.gpuvm_set_remote_first(vm, 4)          # reads in place until a page has cost its migration
 
             def run():
                 gv.gpuvm_reset(vm)
