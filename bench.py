@@ -1097,8 +1097,9 @@ def sweep_remote_first(gv, torch, np, inputs, oracle):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the paged view is a per-GPU "
-              "structure; see DESIGN.md for how it would shard); use --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the paged view is a per-GPU structure: with "
+              "several GPUs each would own a frame pool and page table over the same host buffer and "
+              "take a slice of the work); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
