@@ -112,6 +112,7 @@ class GatherWorkload:
     """Random gather: 64 MiB uint32 host array, 4 KiB pages, 16 MiB pool, 2^20 indices."""
     name = "random_gather_64MiB_u32_4KiB_pages_16MiB_pool_2^20_idx"
     n_elems, n_idx, page, pool = 1 << 24, 1 << 20, 4096, 16 << 20
+    par_baseline = True                              # has an all-cores leg (oracle loops under a parallel-for)
     dtype = "u32"
     kernel = "k_gather"
 
@@ -135,11 +136,12 @@ class GatherWorkload:
         got = self.d_out.cpu().numpy().view(self.np.uint32)
         return bool(self.np.array_equal(got, want))
 
-    def cpu_baseline(self, oracle):
+    def cpu_baseline(self, oracle, par=False):
+        fn = oracle.par_gather if par else oracle.gather
         reps, t = 0, 0.0
-        while t < 10.0 and reps < 5000:                 # about ten seconds of CPU work
+        while t < (3.0 if par else 10.0) and reps < 5000:   # about ten seconds of CPU work on the oracle itself
             t0 = time.perf_counter()
-            oracle.gather(self.data, self.idx)
+            fn(self.data, self.idx)
             t += time.perf_counter() - t0
             reps += 1
         return t / reps, f"whole workload (2^20 gathers on the 64 MiB array), mean of {reps} runs"
@@ -216,6 +218,7 @@ class StreamWorkload:
     """Streaming read-reduce: 8 GiB fp32 host array, 64 KiB pages, 2 GiB pool, 3 passes."""
     name = "stream_reduce_8GiB_f32_64KiB_pages_2GiB_pool_3_passes"
     n_floats, page, pool, passes, block = 1 << 31, 65536, 2 << 30, 3, 1 << 18
+    par_baseline = True                              # has an all-cores leg (oracle loops under a parallel-for)
     dtype = "f64"
     kernel = "k_stream_reduce"
 
@@ -237,21 +240,23 @@ class StreamWorkload:
             self.gv.gpuvm_run_stream_reduce(self.vm, self.block, self.d_s[p])
 
     def verify(self, oracle):
+        """Every block of every pass against the oracle's sum of the same block
+        (the data do not change between passes, so one oracle pass serves all)."""
         np = self.np
         got = self.d_s.cpu().numpy()
-        blocks = np.linspace(0, self.nblocks - 1, 64).astype(np.int64)      # sampled blocks
         ok = True
-        for b in blocks:
-            x = self.arr[b * self.block:(b + 1) * self.block]
-            want = oracle.stream_reduce(x, self.block, 1)[0, 0]
-            scale = oracle.stream_abs(x, self.block)[0]
-            ok &= bool(np.all(np.abs(got[:, b] - want) <= 1e-5 * scale))
+        step = 1 << 10                                              # 1024 blocks = 1 GiB at a time
+        for b0 in range(0, self.nblocks, step):
+            x = self.arr[b0 * self.block:(b0 + step) * self.block]
+            want = oracle.stream_reduce(x, self.block, 1)[0]
+            scale = oracle.stream_abs(x, self.block)
+            ok &= bool(np.all(np.abs(got[:, b0:b0 + step] - want[None, :]) <= 1e-5 * scale[None, :]))
         return ok
 
-    def cpu_baseline(self, oracle):
+    def cpu_baseline(self, oracle, par=False):
         n = 1 << 28                                                  # 1 GiB of the 8 GiB array, one pass
         t0 = time.perf_counter()
-        oracle.stream_reduce(self.arr[:n], self.block, 1)
+        (oracle.par_stream_reduce if par else oracle.stream_reduce)(self.arr[:n], self.block, 1)
         t = time.perf_counter() - t0
         return t * (self.n_floats / n) * self.passes, "1 GiB of the 8 GiB array, one pass, scaled to 3 passes of 8 GiB"
 
@@ -325,6 +330,7 @@ class BfsWorkload:
     (4 GiB) paged from host in 64 KiB pages, pool = 25 % of col_idx; row_ptr and
     level live in plain HBM."""
     scale, edge_factor, page = 26, 16, 65536
+    par_baseline = True                              # has an all-cores leg (oracle loops under a parallel-for)
     dtype = "i32"
     kernel = "k_bfs_level_balanced"
     naive = False                                    # True: vertex-chunk work distribution (plain CSR)
@@ -361,10 +367,11 @@ class BfsWorkload:
         self._rp = rp
         return bool(np.array_equal(got, want))
 
-    def cpu_baseline(self, oracle):
+    def cpu_baseline(self, oracle, par=False):
         t0 = time.perf_counter()
-        oracle.bfs(self._rp, self.arr, 0)
-        return time.perf_counter() - t0, "whole workload (queue BFS over the full graph)"
+        (oracle.par_bfs if par else oracle.bfs)(self._rp, self.arr, 0)
+        return time.perf_counter() - t0, ("whole workload (one sweep over the vertices per level)" if par
+                                          else "whole workload (queue BFS over the full graph)")
 
     def config(self):
         return {"vertices": self.nv, "edges": int(self.arr.size), "levels": self.levels}
@@ -395,6 +402,7 @@ class BfsWorkload:
 
 class CcWorkload(BfsWorkload):
     """Weakly connected components (label propagation, edge-balanced) on the BFS graph."""
+    par_baseline = False
     kernel = "k_cc_round_balanced"
 
     def __init__(self, gv, torch, np, inputs, policy, scale=None):
@@ -420,6 +428,7 @@ class CcWorkload(BfsWorkload):
 class SsspWorkload(BfsWorkload):
     """SSSP from vertex 0 on the BFS graph; col_idx and the uint32 weights (1..64)
     are both paged from host, each with a pool of 25 % of its size."""
+    par_baseline = False
     kernel = "k_sssp_round_balanced"
 
     def __init__(self, gv, torch, np, inputs, policy, scale=None):
@@ -583,6 +592,7 @@ class EmbeddingWorkload:
     pages, 6.4 GB pool, 20 batches of 65536 bags x 32 Zipf(1.05) ids, sum pooling."""
     rows, dim, page, pool = 50_000_000, 128, 65536, 6_400_000_000
     bags, bag_len, batches = 65536, 32, 20
+    par_baseline = True                              # has an all-cores leg (oracle loops under a parallel-for)
     dtype = "f32"
     kernel = "k_embedding_bag"
     name = "embedding_bag_5e7x128_f32_64KiB_pages_6.4GB_pool_20x65536x32_zipf1.05"
@@ -609,22 +619,30 @@ class EmbeddingWorkload:
         for b in range(self.batches):
             self.gv.gpuvm_run_embedding_bag(self.vm, self.dim, self.d_ids[b], self.bags, self.bag_len, self.d_out[b])
 
-    def verify(self, oracle, sample_bags=512):
+    def verify(self, oracle, sample_bags=512, whole_batches=(0, -1)):
+        """Bit-exact against the ordered-fp32 oracle: every bag of the first and the
+        last batch (cold pool, and the pool after 19 batches of turnover), and
+        `sample_bags` evenly spaced bags of each batch in between."""
         np = self.np
         got = self.d_out.cpu().numpy()
         ok = True
+        whole = {b % self.batches for b in whole_batches}
         pick = np.linspace(0, self.bags - 1, sample_bags).astype(np.int64)
         for b in range(self.batches):
-            ids = np.ascontiguousarray(self.ids[b][pick])
-            ok &= bool(np.array_equal(got[b][pick], oracle.embedding_bag_f32(self.arr, ids)))
+            if b in whole:
+                ok &= bool(np.array_equal(got[b], oracle.embedding_bag_f32(self.arr, np.ascontiguousarray(self.ids[b]))))
+            else:
+                ids = np.ascontiguousarray(self.ids[b][pick])
+                ok &= bool(np.array_equal(got[b][pick], oracle.embedding_bag_f32(self.arr, ids)))
         return ok
 
-    def cpu_baseline(self, oracle):
-        ids = np_contig(self.np, self.ids[0][:4096])
+    def cpu_baseline(self, oracle, par=False):
+        k = 65536 if par else 4096
+        ids = np_contig(self.np, self.ids[0][:k])
         t0 = time.perf_counter()
-        oracle.embedding_bag_f32(self.arr, ids)
+        (oracle.par_embedding_bag_f32 if par else oracle.embedding_bag_f32)(self.arr, ids)
         t = time.perf_counter() - t0
-        return t * (self.bags / 4096) * self.batches, "4096 bags of batch 0, scaled to 20 x 65536 bags"
+        return t * (self.bags / k) * self.batches, f"{k} bags of batch 0, scaled to 20 x 65536 bags"
 
     def config(self):
         return {"rows": self.rows, "dim": self.dim, "bags": self.bags, "bag_len": self.bag_len, "batches": self.batches}
@@ -673,7 +691,7 @@ class EmbeddingWorkload:
             for bt in range(self.batches):
                 gv.gpuvm_bench_embedding_bag_zero_copy(self.vm, self.dim, self.d_ids[bt], self.bags, self.bag_len, self.d_out[bt])
         ms = best_ms(all_batches, reps=2)
-        res["zero_copy_pinned_host_whole_job"] = {"best_ms": round(ms, 2), "parity": self.verify(oracle, sample_bags=64),
+        res["zero_copy_pinned_host_whole_job"] = {"best_ms": round(ms, 2), "parity": self.verify(oracle, sample_bags=64, whole_batches=()),
                                                   "row_GBps": round(self.useful_bytes / ms / 1e6, 1)}
         dev_rows = torch.from_numpy(sub).cuda()
         long_ids = d_ids.long()
@@ -691,6 +709,7 @@ class ScatterWorkload:
     """Scatter-increment with write-back: 32 GiB uint64 host array, 64 KiB pages,
     8 GiB pool, 2^28 atomic +1 at Zipf(0.9) indices, then flush."""
     n_elems, n_upd, page, pool = 1 << 32, 1 << 28, 65536, 8 << 30
+    par_baseline = True                              # has an all-cores leg (oracle loops under a parallel-for)
     dtype = "u64"
     kernel = "k_scatter_inc"
     name = "scatter_increment_32GiB_u64_64KiB_pages_8GiB_pool_2^28_zipf0.9_then_flush"
@@ -720,29 +739,40 @@ class ScatterWorkload:
         self.rounds += 1
 
     def verify(self, oracle):
+        """The whole 32 GiB array, without a second one: (1) the hot head of 2^22
+        counters against the oracle run on an array of that size; (2) EVERY
+        touched position holds its count - the sorted indices, run-length
+        encoded, against the array read at those positions; (3) the grand total
+        of the unsigned array equals the number of updates, which with (2)
+        proves every untouched element zero."""
         np = self.np
-        head = 1 << 22                                # the oracle computes the hot head exactly
+        head = 1 << 22
         want = np.zeros(head, np.uint64)
         oracle.scatter_increment(want, self.idx[self.idx < head])
         ok = bool(np.array_equal(self.arr[:head], want * np.uint64(self.rounds)))
+        srt = np.sort(self.idx)
+        starts = np.flatnonzero(np.concatenate(([True], srt[1:] != srt[:-1])))
+        pos = srt[starts]
+        cnt = np.diff(np.concatenate((starts, [srt.size]))).astype(np.uint64)
+        del srt, starts
+        assert int(cnt.sum()) == self.n_upd
+        self.touched = int(pos.size)
+        for lo in range(0, pos.size, 1 << 24):
+            sl = slice(lo, lo + (1 << 24))
+            ok &= bool(np.array_equal(self.arr[pos[sl]], cnt[sl] * np.uint64(self.rounds)))
         total = 0
-        for lo in range(0, self.n_elems, 1 << 28):    # every update landed exactly once
+        for lo in range(0, self.n_elems, 1 << 28):
             total += int(self.arr[lo:lo + (1 << 28)].sum(dtype=np.uint64))
         ok &= total == self.rounds * self.n_upd
-        tail = np.unique(self.idx[-(1 << 20):])       # sampled cold elements, counted one by one
-        tail = tail[tail >= head][:2000]
-        srt = np.sort(self.idx)
-        cnt = np.searchsorted(srt, tail, "right") - np.searchsorted(srt, tail, "left")
-        ok &= bool(np.array_equal(self.arr[tail], (cnt * self.rounds).astype(np.uint64)))
         return ok
 
-    def cpu_baseline(self, oracle):
-        n = 1 << 22
+    def cpu_baseline(self, oracle, par=False):
+        n = 1 << (24 if par else 22)
         small = self.np.zeros(self.n_elems >> 6, self.np.uint64)
         t0 = time.perf_counter()
-        oracle.scatter_increment(small, self.idx[:n] >> 6)
+        (oracle.par_scatter_increment if par else oracle.scatter_increment)(small, self.idx[:n] >> 6)
         t = time.perf_counter() - t0
-        return t * (self.n_upd / n), "2^22 of the 2^28 updates on a 1/64-size array, scaled"
+        return t * (self.n_upd / n), f"2^{24 if par else 22} of the 2^28 updates on a 1/64-size array, scaled"
 
     def config(self):
         return {"elements": self.n_elems, "updates": self.n_upd}
@@ -1219,17 +1249,54 @@ def main():
                 out["roofline"]["traffic"] = int((kv["host_link_read"] + kv["hbm_read"] + kv["hbm_write"]) * scale)
                 out["roofline"]["traffic_detail"] = {k: int(v * scale) for k, v in kv.items() if k != "faults"}
                 out["roofline"]["traffic_source"] = "profiles/traffic_per_launch.txt (rocprofv3 --pmc), scaled by this run's fault count"
+    # one more cold step, untimed, with the per-access counters on: what the
+    # wavefront dedup and the inter-wave arbitration did (they are off in the
+    # timed steps, where they would cost two ballots loops per access)
+    if args.workload in ("gather", "filter", "matvec_t", "matvec"):
+        gv.gpuvm_configure(W.vm, 0, True)
+        step()
+        gv.gpuvm_check(W.vm)
+        sd = gv.gpuvm_stats(W.vm)
+        gv.gpuvm_configure(W.vm, 0, False)
+        groups = max(sd["wave_page_groups"], 1)
+        out["dedup"] = {
+            "lane_accesses": sd["wave_page_groups"] + sd["lanes_coalesced"],
+            "wave_page_groups": sd["wave_page_groups"], "lanes_coalesced": sd["lanes_coalesced"],
+            "lanes_per_group": round((sd["wave_page_groups"] + sd["lanes_coalesced"]) / groups, 3),
+            "hits": sd["hits"], "faults": sd["faults"], "loading_waits": sd["loading_waits"],
+            "share_of_groups_that_waited_for_another_wave": round(sd["loading_waits"] / groups, 4),
+            "note": "one untimed cold step with access statistics on",
+        }
+    job = {"gpu_paging": round(step_s, 6)}
     if hasattr(W, "baselines"):
         out["baselines_same_gpu"] = W.baselines(oracle)
+        for k, v in out["baselines_same_gpu"].items():
+            if isinstance(v, dict) and k.startswith("zero_copy"):
+                ms = v.get("best_ms", v.get("ms"))
+                if ms:
+                    job["gpu_zero_copy"] = round(ms * 1e-3, 6)
     if not args.no_cpu_baseline:
         cpu_s, sample = W.cpu_baseline(oracle)
+        useful = W.useful_bytes or 0
+        job["cpu_oracle_1_core"] = round(cpu_s, 6)
         out["cpu_baseline"] = {
-            "value": round(st["bytes_in"] / cpu_s / 1e9, 3), "unit": "GB/s",
-            "cores": 1, "kind": "oracle", "sample": sample,
-            "seconds_per_step": round(cpu_s, 6),
-            "note": "the oracle computes the job directly on host memory; value = the page bytes the GPU path "
-                    "serviced for the same job / oracle time, so that both sides are in the metric's unit",
+            "value": round(useful / cpu_s / 1e9, 4) if useful else None, "unit": "useful GB/s",
+            "cores": 1, "kind": "oracle", "sample": sample, "job_seconds": round(cpu_s, 6),
+            "gpu_useful_GBps": out["useful_GBps"],
+            "note": "useful bytes = what the application asked for; the same figure for the GPU path is useful_GBps",
         }
+        if getattr(W, "par_baseline", False):
+            par_s, par_sample = W.cpu_baseline(oracle, par=True)
+            cores = oracle.par_threads()
+            job[f"cpu_parallel_for_{cores}_cores"] = round(par_s, 6)
+            out["cpu_baseline_all_cores"] = {
+                "value": round(useful / par_s / 1e9, 4) if useful else None, "unit": "useful GB/s",
+                "cores": cores, "kind": "the oracle's loops under an OpenMP parallel-for (separate build)",
+                "sample": par_sample, "job_seconds": round(par_s, 6),
+            }
+    out["job_seconds"] = job
+    if "gpu_zero_copy" in job:                       # the shortfall (or gain) against reading host memory in place
+        out["paging_vs_zero_copy_same_gpu"] = round(job["gpu_zero_copy"] / job["gpu_paging"], 4)
     print(json.dumps(out), flush=True)
     gv.gpuvm_destroy(W.vm)
     gv.free_pinned(W.arr)

@@ -48,8 +48,8 @@ enum {
     GPUVM_POLICY_CLOCK_WRITE_AWARE = 3, /* CLOCK that spares a DIRTY page one more time
                                before evicting it, so that clean (read-mostly) pages
                                go first and written ones are written back less often
-                               (paper: Comparisons with UVM - "delay its eviction and
-                               evict one of the least needed read-intensive pages")   */
+                               (paper: Comparisons with UVM, on write-intensive pages;
+                               the paper names the idea, this is one concrete form)   */
     GPUVM_POLICY_GCLOCK = 4, /* generalized CLOCK (not in the paper; the classical GCLOCK
                                with a small counter): a use count of 0..2 per page
                                instead of the bit - installed at 0, raised by every

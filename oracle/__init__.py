@@ -21,6 +21,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gpuvm_oracle.c")
 _LIB = os.path.join(_HERE, "libgpuvm_oracle.so")
+_SRC_PAR = os.path.join(_HERE, "gpuvm_oracle_par.c")
+_LIB_PAR = os.path.join(_HERE, "libgpuvm_oracle_par.so")
 
 FIFO, CLOCK, CLOCK_WA, GCLOCK = 0, 1, 3, 4
 READ, WRITE, ADD = 0, 1, 2
@@ -29,7 +31,13 @@ COUNTER_NAMES = ("faults", "hits", "evictions", "writebacks_evict",
 
 
 def build(force=False):
-    """Compile the oracle with gcc (no optimisation tricks, no OpenMP)."""
+    """Compile the oracle with gcc (no optimisation tricks, no OpenMP), and the
+    separate all-cores build of the Part 1 loops that only the benchmark's
+    cpu_baseline leg times (the same loops under an OpenMP parallel-for)."""
+    if (force or not os.path.exists(_LIB_PAR)
+            or os.path.getmtime(_LIB_PAR) < os.path.getmtime(_SRC_PAR)):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+                               "-Wall", "-Wextra", "-o", _LIB_PAR, _SRC_PAR])
     if (not force and os.path.exists(_LIB)
             and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
         return _LIB
@@ -239,6 +247,75 @@ def filter_sum(key, val, threshold):
     s = np.zeros(1, np.uint64)
     lib().oracle_filter_sum(_p(key), _p(val), key.size, threshold, _p(c), _p(s))
     return int(c[0]), int(s[0])
+
+
+# ---------------------------------------------------------------- Part 1 on all cores (benchmark baseline only)
+
+_par = None
+
+
+def par_lib():
+    global _par
+    if _par is None:
+        build()
+        L = C.CDLL(_LIB_PAR)
+        vp, u64, i64 = C.c_void_p, C.c_uint64, C.c_int64
+        L.par_threads.restype = C.c_int
+        L.par_gather.argtypes = [vp, vp, u64, vp, vp]
+        L.par_stream_reduce.argtypes = [vp, u64, u64, C.c_int, vp]
+        L.par_bfs.argtypes = [vp, vp, i64, i64, vp]
+        L.par_embedding_bag_f32.argtypes = [vp, u64, vp, u64, u64, vp]
+        L.par_scatter_increment.argtypes = [vp, vp, u64]
+        _par = L
+    return _par
+
+
+def par_threads():
+    """Threads the all-cores leg runs on (OpenMP's choice: the cores the process may use)."""
+    return int(par_lib().par_threads())
+
+
+def par_gather(host, idx):
+    host = _arr(host, np.uint32)
+    idx = _arr(idx, np.uint32)
+    assert idx.size == 0 or int(idx.max()) < host.size
+    out = np.empty(idx.size, np.uint32)
+    s = np.zeros(1, np.uint64)
+    par_lib().par_gather(_p(host), _p(idx), idx.size, _p(out), _p(s))
+    return out, int(s[0])
+
+
+def par_stream_reduce(x, block_elems, passes):
+    x = _arr(x, np.float32)
+    nb = (x.size + block_elems - 1) // block_elems
+    s = np.empty((passes, nb), np.float64)
+    par_lib().par_stream_reduce(_p(x), x.size, block_elems, passes, _p(s))
+    return s
+
+
+def par_bfs(row_ptr, col_idx, src=0):
+    row_ptr = _arr(row_ptr, np.int64)
+    col_idx = _arr(col_idx, np.int32)
+    nv = row_ptr.size - 1
+    assert 0 <= src < nv and row_ptr[-1] == col_idx.size
+    level = np.empty(nv, np.int32)
+    par_lib().par_bfs(_p(row_ptr), _p(col_idx), nv, src, _p(level))
+    return level
+
+
+def par_embedding_bag_f32(table, ids):
+    table, ids = _bag_args(table, ids)
+    out = np.empty((ids.shape[0], table.shape[1]), np.float32)
+    par_lib().par_embedding_bag_f32(_p(table), table.shape[1], _p(ids), ids.shape[0], ids.shape[1], _p(out))
+    return out
+
+
+def par_scatter_increment(host, idx):
+    assert host.dtype == np.uint64 and host.flags.c_contiguous
+    idx = _arr(idx, np.uint32)
+    assert idx.size == 0 or int(idx.max()) < host.size
+    par_lib().par_scatter_increment(_p(host), _p(idx), idx.size)
+    return host
 
 
 # ---------------------------------------------------------------- Part 2

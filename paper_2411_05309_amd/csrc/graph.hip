@@ -43,6 +43,7 @@ __global__ __launch_bounds__(kBlock) void k_bfs_level(gpuvm_dev_t vm, const int6
                 }
                 for (int64_t i = pos + lane; i < stop; i += 64) {
                     const int32_t u = (int32_t)gpuvm_frame_load_b32(vm, ptr, (unsigned int)(i - page_first) << 2);
+                    if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); continue; }   // malformed neighbour id
                     if (level[u] < 0) { level[u] = cur + 1; found = 1; }
                 }
                 pos = stop;
@@ -177,12 +178,13 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
 
 template <bool DIRECT>
 __global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
-                                                                const unsigned int *__restrict__ page_owner,
+                                                                const unsigned int *__restrict__ page_owner, int64_t nv,
                                                                 int32_t *level, int32_t cur, int *changed) {
     int found = 0;
     walk_owned_pages<DIRECT>(vm, nullptr, row_ptr, page_owner,
                      [&](int64_t v) { return level[v] == cur; },
                      [&](int64_t, int32_t u, unsigned int, const char *, bool) {
+                         if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); return; }   // malformed neighbour id
                          if (level[u] < 0) { level[u] = cur + 1; found = 1; }
                      });
     if (__builtin_amdgcn_ballot_w64(found != 0) && (threadIdx.x & 63) == 0) *changed = 1;
@@ -192,12 +194,13 @@ __global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, c
 // edge (v, u) and pulls both labels down to the smaller one; the fixed point
 // labels each vertex with the smallest vertex id of its component.
 __global__ __launch_bounds__(kBlock) void k_cc_round_balanced(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
-                                                               const unsigned int *__restrict__ page_owner,
+                                                               const unsigned int *__restrict__ page_owner, int64_t nv,
                                                                int32_t *label, int *changed) {
     int found = 0;
     walk_owned_pages(vm, nullptr, row_ptr, page_owner,
                      [&](int64_t) { return true; },
                      [&](int64_t v, int32_t u, unsigned int, const char *, bool) {
+                         if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); return; }
                          const int32_t lv = __hip_atomic_load(label + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                          const int32_t lu = __hip_atomic_load(label + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                          if (lv < lu) {
@@ -216,13 +219,14 @@ __global__ __launch_bounds__(kBlock) void k_cc_round_balanced(gpuvm_dev_t vm, co
 // Edge weights are a second paged array with the layout of col_idx.
 __global__ __launch_bounds__(kBlock) void k_sssp_round_balanced(gpuvm_dev_t vm, gpuvm_dev_t vmw,
                                                                  const int64_t *__restrict__ row_ptr,
-                                                                 const unsigned int *__restrict__ page_owner,
+                                                                 const unsigned int *__restrict__ page_owner, int64_t nv,
                                                                  uint32_t *dist, const unsigned char *act_cur,
                                                                  unsigned char *act_next, int *changed) {
     int found = 0;
     walk_owned_pages(vm, &vmw, row_ptr, page_owner,
                      [&](int64_t v) { return act_cur[v] != 0; },
                      [&](int64_t v, int32_t u, unsigned int off, const char *pw, bool in_place) {
+                         if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); return; }
                          const uint32_t w = in_place ? __builtin_amdgcn_raw_buffer_load_b32(make_rsrc(pw, 1u << vmw.page_shift), off, 0, GPUVM_AUX_SYSTEM)
                                                      : gpuvm_frame_load_b32(vmw, pw, off);
                          const uint32_t dv = __hip_atomic_load(dist + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -263,10 +267,10 @@ static int run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t sr
         int changed = 0;
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
         if (direct)
-            k_bfs_level_balanced<true><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner,
+            k_bfs_level_balanced<true><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv,
                                                                                  d_level, cur, vm->bfs_changed);
         else if (balanced)
-            k_bfs_level_balanced<false><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner,
+            k_bfs_level_balanced<false><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv,
                                                                                   d_level, cur, vm->bfs_changed);
         else
             k_bfs_level<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, nv, d_level, cur, vm->bfs_changed);
@@ -316,7 +320,7 @@ int gpuvm_run_cc_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int
     for (;;) {
         int changed = 0;
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
-        k_cc_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, d_label,
+        k_cc_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv, d_label,
                                                                       vm->bfs_changed);
         HIP_TRY(hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
@@ -355,7 +359,7 @@ int gpuvm_run_sssp_balanced(gpuvm_t *vm, gpuvm_t *vm_weights, const int64_t *d_r
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
         k_fill8<<<1024, 256, 0, s>>>(next, (size_t)nv, 0);
         k_sssp_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, vm_weights->dev, d_row_ptr,
-                                                                        vm->page_owner, d_dist, cur, next,
+                                                                        vm->page_owner, nv, d_dist, cur, next,
                                                                         vm->bfs_changed);
         hipError_t e = hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);

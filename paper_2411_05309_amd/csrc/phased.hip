@@ -15,6 +15,7 @@ __global__ __launch_bounds__(kBlock) void k_phase_lookup(gpuvm_dev_t vm, const u
     const size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= k) return;
     first[i] = 0;
+    if (aborted(vm)) return;                                          // an earlier phase failed: touch nothing more
     const unsigned long long e = idx[i];
     if (e >= n_elems) { raise_error(vm, GPUVM_ERANGE); return; }
     const unsigned int page = (unsigned int)((e << elem_shift) >> vm.page_shift);
@@ -37,6 +38,10 @@ __global__ __launch_bounds__(kBlock) void k_phase_lookup(gpuvm_dev_t vm, const u
 __global__ __launch_bounds__(1024) void k_phase_assign(gpuvm_dev_t vm, const unsigned int *miss, unsigned int *sorted,
                                                         phase_job *jobs, unsigned int *ctr) {
     const unsigned int n = ctr[0];
+    if (aborted(vm)) {                                                // uniform: the error word is only ever set once
+        if (threadIdx.x == 0) { ctr[0] = 0; ctr[1] = 0; ctr[2] = 0; }
+        return;
+    }
     for (unsigned int i = threadIdx.x; i < n; i += blockDim.x) {
         const unsigned int x = miss[i];
         unsigned int r = 0;
@@ -135,7 +140,12 @@ __global__ __launch_bounds__(kBlock) void k_phase_access(gpuvm_dev_t vm, const u
                                                           uint32_t *out, unsigned long long *sum) {
     const size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
     unsigned long long acc = 0;
-    if (i < k && idx[i] < n_elems) {
+    // a phase that was refused (more pages than frames, or no victim found) has
+    // installed nothing, or only some of its pages: its accesses are dropped
+    // and no pin is given back that was never taken; the launch reports the
+    // error and the handle is good again after gpuvm_reset
+    const bool failed = aborted(vm);
+    if (!failed && i < k && idx[i] < n_elems) {
         const unsigned long long byte = (unsigned long long)idx[i] << (OP == 0 ? 2 : 3);
         const unsigned int page = (unsigned int)(byte >> vm.page_shift);
         const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));

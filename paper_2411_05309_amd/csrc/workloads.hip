@@ -282,7 +282,11 @@ __global__ __launch_bounds__(kBlock) void k_matvec_t(gpuvm_dev_t vm, unsigned lo
                                                       unsigned int window, unsigned int *progress,
                                                       const float *__restrict__ x, double *__restrict__ y) {
     const unsigned int lane = threadIdx.x & 63;
-    const unsigned int n_compute_waves = ((gridDim.x - helper_blocks) * kBlock) >> 6;
+    // compute waves that own a block of 64 columns; the grid is rounded up to whole
+    // workgroups, and a wave without columns never publishes a row: it must not
+    // count as the slowest one
+    const unsigned int n_compute_waves =
+        (unsigned int)min((unsigned long long)(((gridDim.x - helper_blocks) * kBlock) >> 6), (cols + 63) >> 6);
     if (blockIdx.x < helper_blocks) {
         const unsigned int hw = (blockIdx.x * kBlock + threadIdx.x) >> 6;
         const unsigned int nh = (helper_blocks * kBlock) >> 6;

@@ -20,3 +20,15 @@ def gpu():
     import paper_2411_05309_amd as gv
     gv.load()          # raises if libgpuvm.so has not been built
     return gv
+
+
+@pytest.fixture
+def say(capsys):
+    """Progress lines of a long test, printed past pytest's capture so that a
+    watcher of the run sees that it is alive."""
+    import time
+
+    def _say(what):
+        with capsys.disabled():
+            print(f"\n[{time.strftime('%H:%M:%S')}] {what}", end="", flush=True)
+    return _say

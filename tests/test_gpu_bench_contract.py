@@ -33,3 +33,12 @@ def test_default_bench_line(gpu):
     assert abs(d["value"] - roof["achieved"]) / d["value"] < 0.02       # wall clock and HIP events agree
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] == 1 and cpu["value"] > 0 and cpu["sample"]
+    assert len(cpu["note"]) < 256 and cpu["unit"] == "useful GB/s" and cpu["job_seconds"] > 0
+    par = d["cpu_baseline_all_cores"]
+    assert par["cores"] >= 1 and par["value"] > 0 and par["job_seconds"] > 0
+    job = d["job_seconds"]
+    assert job["gpu_paging"] > 0 and job["cpu_oracle_1_core"] > 0 and job["gpu_zero_copy"] > 0
+    assert any(k.startswith("cpu_parallel_for_") for k in job)
+    dd = d["dedup"]                                                      # wavefront dedup and arbitration, in numbers
+    assert dd["wave_page_groups"] + dd["lanes_coalesced"] == dd["lane_accesses"] == d["config"]["indices"]
+    assert dd["hits"] + dd["faults"] == dd["wave_page_groups"] and dd["lanes_per_group"] >= 1.0

@@ -132,6 +132,30 @@ def test_phase_with_more_pages_than_frames_is_refused(gpu):
         assert e.value.code == gv.EDEADLK
 
 
+def test_refused_phase_leaves_the_data_alone(gpu):
+    """A deterministic scatter whose second phase touches more pages than there are
+    frames: the launch reports GPUVM_EDEADLK, the refused phase and every later one
+    change nothing (no update lands in some other page's frame), and after a
+    reset the host array holds exactly the first phase's increments."""
+    n64, page, frames, phase_len = 1 << 15, 4096, 8, 32
+    per_page = page // 8
+    good = (np.arange(phase_len, dtype=np.uint32) % 4) * per_page + 5       # 4 pages
+    wide = np.arange(phase_len, dtype=np.uint32) * per_page + 9             # 32 pages > 8 frames
+    idx = np.concatenate([good, wide, good]).astype(np.uint32)
+    want = np.zeros(n64, np.uint64)
+    oracle.scatter_increment(want, good)
+    with Backing(np.zeros(n64, np.uint64), page, frames * page) as b:
+        with pytest.raises(gv.GpuvmError) as e:
+            gv.gpuvm_run_scatter_increment_phased(b.vm, dev(idx), idx.size, phase_len)
+        assert e.value.code == gv.EDEADLK
+        gv.gpuvm_reset(b.vm)                                       # writes the dirty frames back, clears the error
+        gv.gpuvm_check(b.vm)
+        assert np.array_equal(b.arr, want)
+        gv.gpuvm_run_scatter_increment_phased(b.vm, dev(good), good.size, phase_len)   # the handle works again
+        gv.gpuvm_flush(b.vm)
+        assert np.array_equal(b.arr, 2 * want)
+
+
 def test_gather_phased_full_size_config(gpu):
     """The headline configuration (64 MiB, 4 KiB pages, 4096 frames, 2^20 uniform
     indices) in phases of 1024 accesses: counts, cursor and the final frame

@@ -229,6 +229,11 @@ def test_sssp_balanced(gpu, scale, page, frames, src):
     (512, 4096, 4096, 64),            # a row = 4 pages; 2048 pages over 64 frames
     (300, 1000, 4096, 16),            # ragged: columns not a multiple of 64, short last page
     (64, 16384, 65536, 8),
+    # sliding window and fault-ahead helpers on (every column block has a wave of its
+    # own and the pool holds 256 rows), 5 working waves in a grid rounded up to 8:
+    # the idle ones must not count as the slowest wave
+    (2048, 320, 4096, 80),
+    (1024, 1000, 4096, 128),          # the same with 16 working waves, ragged columns
 ])
 def test_matvec_t_column_order(gpu, rows, cols, page, frames):
     A = inputs.f32_uniform(3, 0, rows * cols).reshape(rows, cols)
@@ -355,6 +360,33 @@ def test_vector_add_overwrite_installs_without_fetching(gpu, n, page, frames):
             gv.gpuvm_run_vector_add_overwrite(ba.vm, bb.vm, bc.vm, n - 3 if (n - 3) * 4 % page else n - 5)
         with pytest.raises(gv.GpuvmError):
             gv.gpuvm_run_vector_add_overwrite(ba.vm, bb.vm, ba.vm, n)
+
+
+def test_graph_launchers_report_bad_neighbour_ids(gpu):
+    """A neighbour id outside [0, nv) - too large, or negative - is reported as
+    GPUVM_ERANGE by every graph launcher instead of becoming a stray write."""
+    nv = 2000
+    rp, ci = inputs.rmat_csr(6, 11)
+    rp, ci = rp[:nv + 1].copy(), ci[:int(rp[nv])].copy() % nv
+    w = inputs.edge_weights(4, 0, ci.size)
+    first = int(rp[0])                                               # an edge of the source vertex: always visited
+    assert rp[1] > rp[0]
+    for bad in (nv, nv + 12345, -1, -(1 << 31)):
+        c2 = ci.copy()
+        c2[first] = bad
+        for name in ("bfs", "bfs_balanced", "cc", "sssp"):
+            with Backing(c2, 4096, 8 * 4096) as b, Backing(w, 4096, 8 * 4096) as bw:
+                d_out = torch.zeros(nv, dtype=torch.int32, device="cuda")
+                with pytest.raises(gv.GpuvmError) as e:
+                    if name == "bfs":
+                        gv.gpuvm_run_bfs(b.vm, dev(rp), nv, 0, d_out)
+                    elif name == "bfs_balanced":
+                        gv.gpuvm_run_bfs_balanced(b.vm, dev(rp), nv, 0, d_out)
+                    elif name == "cc":
+                        gv.gpuvm_run_cc_balanced(b.vm, dev(rp), nv, d_out)
+                    else:
+                        gv.gpuvm_run_sssp_balanced(b.vm, bw.vm, dev(rp), nv, 0, d_out)
+                assert e.value.code == gv.ERANGE, (name, bad)
 
 
 def test_bfs_zero_copy_baseline_matches_the_oracle(gpu):

@@ -300,3 +300,26 @@ def test_vector_add_is_ieee_fp32_addition():
     exact = a.astype(np.float64) + b.astype(np.float64)
     assert np.all(np.abs(c - exact) <= np.abs(exact) * 2.0 ** -24 + 1e-45)  # correctly rounded
     assert oracle.vector_add(np.array([1.0, -2.5], np.float32), np.array([2.0, 2.5], np.float32)).tolist() == [3.0, 0.0]
+
+
+# ---------------------------------------------------------------- the all-cores build of the same loops
+
+def test_parallel_for_leg_equals_the_sequential_oracle():
+    """oracle/gpuvm_oracle_par.c is timed by the benchmark's cpu_baseline leg only;
+    it must return what the sequential definitions return."""
+    assert oracle.par_threads() >= 1
+    data = inputs.u32_values(1, 0, 1 << 16)
+    idx = inputs.u32_indices(2, 0, 30011, 1 << 16)
+    a, b = oracle.gather(data, idx), oracle.par_gather(data, idx)
+    assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+    x = inputs.f32_uniform(7, 0, (1 << 18) + 333)
+    assert np.array_equal(oracle.stream_reduce(x, 4096, 2), oracle.par_stream_reduce(x, 4096, 2))   # same order inside a block
+    rp, ci = inputs.rmat_csr(5, 13)
+    for src in (0, 77):
+        assert np.array_equal(oracle.bfs(rp, ci, src), oracle.par_bfs(rp, ci, src))
+    table = inputs.f32_uniform(11, 0, 512 * 64).reshape(512, 64)
+    ids = inputs.u32_indices(3, 0, 200 * 9, 512).astype(np.int32).reshape(200, 9)
+    assert np.array_equal(oracle.embedding_bag_f32(table, ids), oracle.par_embedding_bag_f32(table, ids))
+    sidx = inputs.scatter_indices(3, 0, 100000, 1 << 12)
+    h1, h2 = np.zeros(1 << 12, np.uint64), np.zeros(1 << 12, np.uint64)
+    assert np.array_equal(oracle.scatter_increment(h1, sidx), oracle.par_scatter_increment(h2, sidx))
