@@ -342,6 +342,24 @@ GPUVM_API int gpuvm_run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_
 GPUVM_API int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x,
                                  double *d_y, void *stream);
 
+/* gpuvm_run_matvec_t for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, result and errors; it calls no hipMalloc / hipFree and no other
+ * allocating routine.  The one scratch buffer of the product (the row every
+ * compute wavefront has reached, 4 bytes per wavefront, which the other entry
+ * point allocates per handle on first use) lives in a static device array of
+ * GPUVM_NOALLOC_MAX_COLS / 64 words = 8 KiB that every GPU the library runs on
+ * holds until the process ends.  cols above GPUVM_NOALLOC_MAX_COLS are refused
+ * with GPUVM_ERANGE (and a line on stderr).  The handle's device must be the
+ * current one (GPUVM_EINVAL otherwise).  All calls on one GPU share the array:
+ * it is cleared by a fill kernel at the start of every call, and calls that
+ * overlap on one GPU (different streams, different handles) race on it - order
+ * them.  The caller still passes inputs and outputs; the handle was created
+ * (and its pool allocated) beforehand. */
+#define GPUVM_NOALLOC_MAX_COLS 131072
+GPUVM_API int gpuvm_run_matvec_t_noalloc(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x,
+                                         double *d_y, void *stream);
+
 /* y = A x over the same kind of matrix, one thread per ROW (the first product
  * of the paper's MVT, the first step of its ATAX): the lanes of a wavefront
  * stand on 64 different pages and walk along their rows.  cols must be a

@@ -96,6 +96,7 @@ _SIGNATURES = {
     "gpuvm_run_embedding_bag": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_bench_embedding_bag_zero_copy": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_matvec_t": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+    "gpuvm_run_matvec_t_noalloc": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_matvec": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_filter_sum": ([C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_scatter_increment": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
@@ -310,6 +311,10 @@ def gpuvm_run_matvec(vm, rows, cols, d_x, d_y, stream=None):
 
 def gpuvm_run_matvec_t(vm, rows, cols, d_x, d_y, stream=None):
     _call("gpuvm_run_matvec_t", vm, rows, cols, _ptr(d_x), _ptr(d_y), _stream(stream))
+
+
+def gpuvm_run_matvec_t_noalloc(vm, rows, cols, d_x, d_y, stream=None):
+    _call("gpuvm_run_matvec_t_noalloc", vm, rows, cols, _ptr(d_x), _ptr(d_y), _stream(stream))
 
 
 def gpuvm_run_filter_sum(vm_key, vm_val, threshold, d_count, d_sum, stream=None):

@@ -5,6 +5,8 @@
 // kernels (System Overview; Register usage).
 #include "gpuvm_internal.h"
 
+#include <atomic>
+
 using namespace gpuvm_detail;
 
 // Random gather: one access per lane per iteration, grid-stride.  (Several
@@ -269,6 +271,17 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
 //    fetch every one itself and falls further behind (measured: 2-3x the
 //    traffic, 8x the time).  The slowest wave is never held back, so the
 //    window always moves; waiting is bounded by spin_limit all the same.
+constexpr unsigned int kRowProgressLen = 8192;        // progress words of a handle's own array
+
+// Scratch of gpuvm_run_matvec_t_noalloc: the row each compute wave has reached,
+// one word per wave, in place of the array the allocating entry point keeps per
+// handle.  One copy per GPU, held until the process ends; every call on a GPU
+// shares it, so calls that overlap on one GPU race.
+constexpr unsigned int kNoAllocWaves = GPUVM_NOALLOC_MAX_COLS / 64;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned int scratch[kNoAllocWaves];
+static std::atomic<unsigned int *> scratch_of_device[kMaxDevices];
+
 __device__ __forceinline__ unsigned int slowest_row(const unsigned int *progress, unsigned int n_compute_waves) {
     unsigned int lo = 0xFFFFFFFFu;
     for (unsigned int i = threadIdx.x & 63; i < n_compute_waves; i += 64) lo = min(lo, a_load(progress + i));
@@ -544,7 +557,9 @@ int gpuvm_bench_embedding_bag_zero_copy(gpuvm_t *vm, size_t dim, const int32_t *
     return run_embedding_bag(vm, dim, d_ids, bags, bag_len, d_out, stream, true);
 }
 
-int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, double *d_y, void *stream) {
+// progress == nullptr: the array of the handle, allocated on first use
+static int run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, double *d_y, void *stream,
+                        unsigned int *progress, unsigned int progress_len) {
     if (!vm || !d_x || !d_y || rows == 0 || cols == 0) return GPUVM_EINVAL;
     if (rows * cols * 4 != vm->dev.bytes) return GPUVM_EINVAL;
     if (rows >= 0xFFFFFFF0ull) return GPUVM_EINVAL;
@@ -561,12 +576,42 @@ int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, 
     // fault-ahead helpers: what is left of the wave budget, at most two per compute unit
     const int helpers = window ? std::min(cap - waves, vm->cus * 2) / kWavesPerBlock * kWavesPerBlock : 0;
     hipStream_t s = (hipStream_t)stream;
-    if (!vm->row_progress) HIP_TRY(hipMalloc(&vm->row_progress, 8192 * sizeof(unsigned int)));
-    k_fill32<<<8, 256, 0, s>>>(vm->row_progress, 8192, 0u);
+    if (!progress) {
+        if (!vm->row_progress) HIP_TRY(hipMalloc(&vm->row_progress, kRowProgressLen * sizeof(unsigned int)));
+        progress = vm->row_progress;
+        progress_len = kRowProgressLen;
+    }
+    if ((unsigned int)waves > progress_len) return GPUVM_EINVAL;      // one word per compute wave
+    k_fill32<<<8, 256, 0, s>>>(progress, progress_len, 0u);            // a fill kernel, not a memset: capturable
     k_matvec_t<<<grid_for_waves(waves) + helpers / kWavesPerBlock, kBlock, 0, s>>>(
-        vm->dev, rows, cols, skew, (unsigned int)(helpers / kWavesPerBlock), window, vm->row_progress, d_x, d_y);
+        vm->dev, rows, cols, skew, (unsigned int)(helpers / kWavesPerBlock), window, progress, d_x, d_y);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
+}
+
+int gpuvm_run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, double *d_y, void *stream) {
+    return run_matvec_t(vm, rows, cols, d_x, d_y, stream, nullptr, 0);
+}
+
+int gpuvm_run_matvec_t_noalloc(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, double *d_y, void *stream) {
+    if (!vm) return GPUVM_EINVAL;
+    if (cols > (size_t)GPUVM_NOALLOC_MAX_COLS) {
+        fprintf(stderr, "libgpuvm: gpuvm_run_matvec_t_noalloc: %zu columns exceed the %d that the static scratch "
+                        "array holds progress words for; use gpuvm_run_matvec_t\n", cols, GPUVM_NOALLOC_MAX_COLS);
+        return GPUVM_ERANGE;
+    }
+    // the address of this device's copy of the array, looked up once per device
+    // with that device current (the array's name is no device address in host code)
+    int device = -1;
+    HIP_TRY(hipGetDevice(&device));
+    if (device != vm->device || device < 0 || device >= kMaxDevices) return GPUVM_EINVAL;
+    unsigned int *p = scratch_of_device[device].load(std::memory_order_acquire);
+    if (!p) {
+        HIP_TRY(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+        if (!p) return GPUVM_EHIP;
+        scratch_of_device[device].store(p, std::memory_order_release);
+    }
+    return run_matvec_t(vm, rows, cols, d_x, d_y, stream, p, kNoAllocWaves);
 }
 
 int gpuvm_run_matvec(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, double *d_y, void *stream) {
