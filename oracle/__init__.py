@@ -79,6 +79,8 @@ def lib():
         L.sim_phase.restype = C.c_int
         L.sim_run.argtypes = [vp, vp, vp, vp, u64, u64, vp]
         L.sim_run.restype = C.c_int
+        L.sim_set_spread.argtypes = [vp, u64]
+        L.sim_set_spread.restype = C.c_int
         L.sim_flush.argtypes = [vp]
         L.sim_counters.argtypes = [vp, vp]
         L.sim_hand.argtypes = [vp]
@@ -323,11 +325,12 @@ def par_scatter_increment(host, idx):
 class PagingSim:
     """Sequential simulator of the circular frame buffer with reference
     counters; policy FIFO, CLOCK, CLOCK_WA (write-aware) or GCLOCK (use count
-    0..2).  ``host`` (uint64 array, modified in place by
+    0..2); ``spread`` > 0 gives the CLOCK policies a front hand that many
+    frames ahead of the cursor (two-handed clock).  ``host`` (uint64 array, modified in place by
     write-backs) is optional: without it only the bookkeeping is simulated and
     ``n_words`` gives the size of the address space in 8-byte words."""
 
-    def __init__(self, page_words, n_frames, policy, host=None, n_words=None):
+    def __init__(self, page_words, n_frames, policy, host=None, n_words=None, spread=0):
         if host is not None:
             assert host.dtype == np.uint64 and host.flags.c_contiguous
             n_words = host.size
@@ -337,6 +340,8 @@ class PagingSim:
         self._s = lib().sim_create(_p(host), n_words, page_words, n_frames, policy)
         if not self._s:
             raise ValueError("sim_create failed")
+        if spread and lib().sim_set_spread(self._s, spread):
+            raise ValueError("a front hand needs a policy with a reference bit")
 
     def close(self):
         if self._s:

@@ -37,6 +37,16 @@
  *       installed at 0, raised by every later use, lowered by the passing
  *       cursor, evicted at 0 - pages earn their chances by being used again,
  *       and a scan never makes the cursor pass anything;
+ *     - two hands (optional, the CLOCK policies only; the classical two-handed
+ *       clock of 4.2BSD, not in the paper): with a spread of S > 0 positions a
+ *       front hand runs S frames ahead of the cursor and clears the reference
+ *       bit of the frame it stands on, every time the cursor advances; the
+ *       cursor itself then passes a frame only if its page was used again
+ *       after the front hand went by (and clears the bit, as before).  A page
+ *       keeps its first bit from its installation until the front hand reaches
+ *       it, so fresh pages are safe for F - S positions, and a page that is
+ *       never used again is taken at the cursor's first visit: a scan makes
+ *       the cursor pass nothing.  S = 0 is the one-handed CLOCK above;
  *     - accesses arrive in phases (a group of accesses that are in flight
  *       together); each distinct page of a phase counts one hit or one fault;
  *       its faults are served in ascending page order; pins are dropped when
@@ -303,6 +313,7 @@ typedef struct sim {
     int64_t *where;        /* per page: frame, -1 = not in GPU memory      */
     uint64_t *frames;      /* n_frames x page_words when host != NULL      */
     uint64_t hand;         /* global head cursor of the circular buffer    */
+    uint64_t spread;       /* two-handed CLOCK: front hand this far ahead, 0 = one hand */
     uint64_t counters[SIM_NCOUNTERS];
     uint8_t *seen;         /* per page scratch: member of current phase    */
 } sim_t;
@@ -360,6 +371,11 @@ static void sim_fault(sim_t *s, uint64_t p)
     for (;;) {
         f = s->hand;
         s->hand = (s->hand + 1) % s->n_frames;
+        if (s->spread && (s->policy == SIM_CLOCK || s->policy == SIM_CLOCK_WA)) {
+            /* the front hand moves with the cursor and clears the bit it stands on */
+            uint64_t g = (f + s->spread) % s->n_frames;
+            if (g != f && s->owner[g] >= 0) s->ref[g] = 0;
+        }
         if (s->owner[f] < 0) break;                       /* never used yet */
         if (s->pin[f] > 0) { s->counters[SIM_C_SKIPS]++; continue; }
         if ((s->policy == SIM_CLOCK || s->policy == SIM_CLOCK_WA) && s->ref[f]) {
@@ -469,6 +485,16 @@ void sim_flush(sim_t *s)
             if (s->policy != SIM_GCLOCK) s->defer[f] = 0;   /* there it is half of the use count */
         }
     }
+}
+
+/* Two-handed CLOCK: distance of the front hand from the cursor, in frames
+ * (0 = one hand; taken modulo the number of frames).  Returns 0, or -1 for a
+ * policy without a reference bit. */
+int sim_set_spread(sim_t *s, uint64_t spread)
+{
+    if (spread && s->policy != SIM_CLOCK && s->policy != SIM_CLOCK_WA) return -1;
+    s->spread = spread % s->n_frames;
+    return 0;
 }
 
 void sim_counters(const sim_t *s, uint64_t *out)

@@ -34,10 +34,10 @@ def _gold(name):
     return rows
 
 
-def _run_pages(pages, frames, policy, writes=None, phase_len=1, n_pages=None):
+def _run_pages(pages, frames, policy, writes=None, phase_len=1, n_pages=None, spread=0):
     """Page-granular trace through the simulator (one word per page)."""
     n_pages = n_pages or (max(pages) + 1)
-    sim = PagingSim(1, frames, policy, n_words=n_pages)
+    sim = PagingSim(1, frames, policy, n_words=n_pages, spread=spread)
     op = None if writes is None else np.where(np.asarray(writes), WRITE, READ).astype(np.uint8)
     sim.run(np.asarray(pages, np.uint64), op=op, phase_len=phase_len)
     return sim
@@ -188,6 +188,129 @@ def test_clock_keeps_a_reused_page_that_fifo_drops():
     assert _run_pages(refs, 3, CLOCK).counters["faults"] == 5
 
 
+# ---------------------------------------------------------------- two-handed CLOCK
+
+def two_hands_rotating_queue_model(refs, frames, spread):
+    """The two-handed clock told as a rotating queue: the ring of frames, seen
+    from the cursor, is a queue whose head is the frame under the cursor (None =
+    never used).  Each step of the cursor first lets the front hand clear the R
+    bit of the element `spread` places behind the head of the queue, then looks
+    at the head: an empty frame or a page with a clear bit gives way to the new
+    page, which goes to the back; a page with its bit set loses the bit and goes
+    to the back itself.  R is set on load and on every use."""
+    q, rbit, faults, passes = deque([None] * frames), {}, 0, 0
+    for p in refs:
+        if p in rbit:
+            rbit[p] = 1
+            continue
+        faults += 1
+        while True:
+            if spread % frames and q[spread % frames] is not None:
+                rbit[q[spread % frames]] = 0
+            head = q.popleft()
+            if head is not None and rbit[head]:
+                rbit[head] = 0
+                q.append(head)
+                passes += 1
+                continue
+            if head is not None:
+                del rbit[head]
+            q.append(p)
+            rbit[p] = 1
+            break
+    return faults, {x for x in q if x is not None}, passes
+
+
+def test_two_hands_exhaustive_small_traces_against_the_rotating_queue():
+    checked = 0
+    for npages, frames, length in [(3, 2, 6), (4, 3, 7), (5, 3, 6), (5, 4, 6)]:
+        for spread in range(1, frames):
+            for refs in itertools.product(range(npages), repeat=length):
+                faults, resident, passes = two_hands_rotating_queue_model(refs, frames, spread)
+                sim = _run_pages(list(refs), frames, CLOCK, n_pages=npages, spread=spread)
+                assert sim.counters["faults"] == faults, (refs, spread)
+                assert sim.counters["sweeps"] == passes, (refs, spread)
+                own = sim.state()["owner"]
+                assert set(own[own >= 0].tolist()) == resident, (refs, spread)
+                checked += 1
+    assert checked > 40000
+
+
+def test_two_hands_long_skewed_traces_against_the_rotating_queue():
+    rng = np.random.default_rng(21)
+    differs = 0
+    for _ in range(40):
+        npages = int(rng.integers(6, 80))
+        frames = int(rng.integers(2, npages))
+        spread = int(rng.integers(1, frames))
+        refs = np.minimum(rng.geometric(0.12, 4000) - 1, npages - 1).tolist()
+        faults, resident, passes = two_hands_rotating_queue_model(refs, frames, spread)
+        sim = _run_pages(refs, frames, CLOCK, n_pages=npages, spread=spread)
+        assert sim.counters["faults"] == faults and sim.counters["sweeps"] == passes
+        own = sim.state()["owner"]
+        assert set(own[own >= 0].tolist()) == resident
+        differs += faults != second_chance_queue_model(refs, frames)[0]
+    assert differs > 20                      # the second hand really changes the outcome
+
+
+def test_front_hand_on_the_cursor_is_the_one_handed_clock():
+    """A spread of 0 or of a whole ring puts the front hand on the cursor's own
+    frame: there is none, and the policy is the second chance of the textbook."""
+    rng = np.random.default_rng(22)
+    for _ in range(20):
+        npages = int(rng.integers(4, 50))
+        frames = int(rng.integers(1, npages))
+        refs = np.minimum(rng.geometric(0.15, 2000) - 1, npages - 1).tolist()
+        want = second_chance_queue_model(refs, frames)[0]
+        for spread in (0, frames, 3 * frames):
+            assert _run_pages(refs, frames, CLOCK, n_pages=npages, spread=spread).counters["faults"] == want
+    with pytest.raises(ValueError):
+        PagingSim(1, 4, FIFO, n_words=8, spread=2)           # no reference bit, no front hand
+
+
+@pytest.mark.parametrize("n,f,t", [(10, 3, 4), (17, 16, 3), (64, 16, 3), (1000, 256, 2)])
+def test_two_hands_pass_nothing_on_a_scan(n, f, t):
+    """Cyclic scan: the front hand has cleared every bit before the cursor
+    arrives, so the closed form of the scan holds with zero passes - where one
+    hand goes once round clearing bits at the start of every lap."""
+    for spread in sorted({1, f // 2, f - 1} - {0}):
+        c = _run_pages(list(range(n)) * t, f, CLOCK, spread=spread).counters
+        assert c["faults"] == t * n and c["evictions"] == t * n - f and c["hits"] == 0
+        assert c["sweeps"] == 0 and c["skips"] == 0
+    one = _run_pages(list(range(n)) * t, f, CLOCK).counters
+    assert one["faults"] == t * n and one["sweeps"] >= f
+
+
+def test_hand_trace_two_hands_f4():
+    """4 frames, front hand 2 ahead, trace 1 2 3 4 2 5 1 3 5 6 (bits as r0..r3).
+
+    Fill: 1 -> frame 0 (front hand on empty frame 2), 2 -> frame 1 (front on
+    empty 3), 3 -> frame 2 (front on frame 0: r0 cleared), 4 -> frame 3 (front
+    on 1: r1 cleared).  Bits 0 0 1 1, cursor 0.  2 hits: r1 set.
+    5: cursor 0, front clears r2; frame 0 (page 1) has a clear bit: evicted, 5
+    installed.  Frames 5 2 3 4, bits 1 1 0 1, cursor 1.
+    1: cursor 1, front clears r3; frame 1 (page 2) has its bit set: cleared and
+    passed (1st pass).  Cursor 2, front clears r0 (page 5); frame 2 (page 3) is
+    clear: evicted, 1 installed.  Frames 5 2 1 4, bits 0 0 1 0, cursor 3.
+    3: cursor 3, front on frame 1 (already clear); frame 3 (page 4) clear:
+    evicted, 3 installed.  Frames 5 2 1 3, bits 0 0 1 1, cursor 0.  5 hits: r0.
+    6: cursor 0, front clears r2; frame 0 (page 5) set: cleared, passed (2nd
+    pass).  Cursor 1, front clears r3; frame 1 (page 2) clear: evicted, 6
+    installed.  Frames 5 6 1 3.  8 faults, 2 hits, 4 evictions, 2 passes.
+
+    One hand: the fill leaves all bits set; 2 hits.  5 clears four bits (4
+    passes) and takes frame 0.  1 takes frame 1 (page 2, clear).  3 and 5 hit.
+    6: frame 2 (page 3) set: 5th pass; frame 3 (page 4) clear: evicted.  Frames
+    5 1 3 6; 7 faults, 3 hits, 3 evictions.
+    """
+    rows = _gold("trace_two_hands_f4.txt")
+    acc = rows[0][1:]
+    pages = [int(a[:-1]) for a in acc]
+    for row in rows[1:]:
+        assert row[1] == "spread"
+        _check_expect(_run_pages(pages, 4, CLOCK, spread=int(row[2])), _parse_expect(row[2:]))
+
+
 # ---------------------------------------------------------------- hand-worked traces
 
 def _parse_expect(row):
@@ -280,9 +403,9 @@ def _check_invariants(sim, n_frames):
     assert np.all(st["dirty"][owner < 0] == 0)
 
 
-@pytest.mark.parametrize("policy", [FIFO, CLOCK])
-def test_random_phases_invariants_and_data(policy):
-    rng = np.random.default_rng(3 + policy)
+@pytest.mark.parametrize("policy,two_hands", [(FIFO, False), (CLOCK, False), (CLOCK, True)])
+def test_random_phases_invariants_and_data(policy, two_hands):
+    rng = np.random.default_rng(3 + policy + 10 * two_hands)
     for trial in range(25):
         page_words = int(rng.choice([1, 4, 16]))
         n_words = int(rng.integers(20, 400))
@@ -291,7 +414,7 @@ def test_random_phases_invariants_and_data(policy):
         phase_len = int(rng.integers(1, frames + 1))
         host = rng.integers(0, 1 << 40, n_words).astype(np.uint64)
         model = host.copy()                 # the same ops on plain memory
-        sim = PagingSim(page_words, frames, policy, host=host)
+        sim = PagingSim(page_words, frames, policy, host=host, spread=frames // 2 if two_hands else 0)
         for _ in range(30):
             k = phase_len
             idx = rng.integers(0, n_words, k).astype(np.uint64)
