@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--workload", default="gather", choices=["gather", "stream", "bfs", "cc", "sssp", "matvec_t", "matvec", "filter", "vector_add", "vector_add_overwrite", "embedding", "scatter"])
     ap.add_argument("--policy", default="clock", choices=["clock", "fifo", "fifo_wait", "clock_write_aware", "gclock"])
     ap.add_argument("--waves-per-cu", type=int, default=0)
+    ap.add_argument("--clock-hands", type=int, default=None, metavar="EIGHTHS",
+                    help="CLOCK policies: front hand this many eighths of the ring ahead of the cursor (0 = one hand; default 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
     ap.add_argument("--remote-first", type=int, default=0, metavar="BYTES",
@@ -554,11 +556,7 @@ class FilterWorkload:
             hv[lo:lo + (1 << 26)].copy_(inputs.t_u32_values(6, lo, 1 << 26, "cuda"))
         torch.cuda.synchronize()
         self.thr = 0xFFFFFFFF - int(self.sel * 2 ** 32)
-        # the key column is scanned once, front to back: the ring as it is (FIFO) is
-        # the policy for it - under CLOCK every frame has its bit set when the hand
-        # arrives, and a whole revolution of bit clearing goes through the one
-        # cursor word while nothing moves over the link (33.3 ms instead of 29.6)
-        self.vm = gv.gpuvm_create(self.arr.ctypes.data, self.arr.nbytes, self.page, self.pool, gv.POLICY_FIFO)
+        self.vm = gv.gpuvm_create(self.arr.ctypes.data, self.arr.nbytes, self.page, self.pool, policy)
         self.vmw = gv.gpuvm_create(self.varr.ctypes.data, self.varr.nbytes, self.page, self.pool, policy)
         self.d_c = torch.zeros(1, dtype=torch.int64, device="cuda")
         self.d_s = torch.zeros(1, dtype=torch.int64, device="cuda")
@@ -584,7 +582,7 @@ class FilterWorkload:
 
     def config(self):
         return {"rows": self.n, "selectivity": self.sel, "matches": getattr(self, "matches", None),
-                "key_column_policy": "fifo", "value_column_faults": self.stats_w["faults"], "value_column_pages": self.n * 4 // self.page}
+                "value_column_faults": self.stats_w["faults"], "value_column_pages": self.n * 4 // self.page}
 
 
 class EmbeddingWorkload:
@@ -826,7 +824,8 @@ def sweep_oversubscription(gv, torch, np, inputs, oracle):
     arr[...] = data
     d_idx = torch.from_numpy(idx.view(np.int32)).cuda()
     d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
-    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("fifo", gv.POLICY_FIFO), ("fifo_wait", gv.POLICY_FIFO_WAIT),
+    for pol_name, pol in (("clock", gv.POLICY_CLOCK), ("clock_one_hand", gv.POLICY_CLOCK), ("clock_hands_6_eighths", gv.POLICY_CLOCK),
+                          ("fifo", gv.POLICY_FIFO), ("fifo_wait", gv.POLICY_FIFO_WAIT), ("gclock", gv.POLICY_GCLOCK),
                           ("clock_remote_first", gv.POLICY_CLOCK)):
         base = None
         for lv in levels:
@@ -834,6 +833,10 @@ def sweep_oversubscription(gv, torch, np, inputs, oracle):
             vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, pool, pol)
             if pol_name.endswith("remote_first"):
                 gv.gpuvm_set_remote_first(vm, 4)          # reads in place until a page has cost its migration
+            if pol_name == "clock_one_hand":
+                gv.gpuvm_set_clock_hands(vm, 0)
+            if pol_name == "clock_hands_6_eighths":
+                gv.gpuvm_set_clock_hands(vm, 6)
 
             def run():
                 gv.gpuvm_reset(vm)
@@ -845,7 +848,8 @@ def sweep_oversubscription(gv, torch, np, inputs, oracle):
             base = base or ms
             print(json.dumps({"sweep": "oversubscription", "workload": "random_gather_64MiB_4KiB_pages", "policy": pol_name,
                               "level": lv, "pool_bytes": pool, "ms": round(ms, 3), "slowdown_vs_level0": round(ms / base, 3),
-                              "faults": st["faults"], "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "parity": ok}), flush=True)
+                              "faults": st["faults"], "passes_per_fault": round(st["alloc_sweeps"] / max(st["faults"], 1), 3),
+                              "link_in_GBps": round(st["bytes_in"] / ms / 1e6, 2), "parity": ok}), flush=True)
             gv.gpuvm_destroy(vm)
     gv.free_pinned(arr)
     scale, page = 24, 65536
@@ -1164,6 +1168,11 @@ def main():
         W.name += "_vertex_chunks"
     if args.waves_per_cu:
         gv.gpuvm_set_waves_per_cu(W.vm, args.waves_per_cu)
+    if args.clock_hands is not None:
+        for vm in (W.vm, getattr(W, "vmw", None), getattr(W, "vmb", None), getattr(W, "vmc", None)):
+            if vm is not None:
+                gv.gpuvm_set_clock_hands(vm, args.clock_hands)
+        W.name += f"_clock_hands_{args.clock_hands}_eighths"
     if args.remote_first:
         for vm in (W.vm, getattr(W, "vmw", None)):            # second paged array: the filter's value column
             if vm is not None:

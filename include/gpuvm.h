@@ -106,6 +106,9 @@ typedef struct gpuvm_dev {
 
 #define GPUVM_F_ACCESS_STATS 1u   /* also count hits / groups / coalesced lanes     */
 #define GPUVM_F_OVERLAPPED_WRITEBACK 2u /* see gpuvm_set_writeback_mode              */
+#define GPUVM_F_HANDS_SHIFT 2          /* bits 2..4: two-handed CLOCK, front hand n_frames * value / 8
+                                          ahead of the cursor; 0 = one hand (gpuvm_set_clock_hands)  */
+#define GPUVM_F_HANDS_MASK 7u
 #define GPUVM_F_REMOTE_SHIFT 8         /* flags >> 8: touches in place before a page
                                           migrates, 0 = every miss migrates (see
                                           gpuvm_set_remote_first)                    */
@@ -149,7 +152,7 @@ GPUVM_API int gpuvm_device_handle(const gpuvm_t *vm, gpuvm_dev_t *out);
  * default); access_stats != 0 turns the per-access counters on. */
 GPUVM_API int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats);
 
-/* How a fault treats a dirty victim.  GPUVM_WB_SERIAL (default): the paper's
+/* How a fault treats a dirty victim.  GPUVM_WB_SERIAL: the paper's
  * order, the write-back completes before the fetch starts.
  * GPUVM_WB_OVERLAPPED: one pass over the frame moves the old content to the
  * host and the new page in, the transfers of both directions in flight
@@ -157,9 +160,31 @@ GPUVM_API int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats
  * paper's vector-addition result shows (Evaluation, "Transfer-bound
  * Applications").  Results are the same; only the time of one fault differs,
  * and with a whole wavefront as the mover and other wavefronts filling the
- * link in the meantime the measured gain is a few per cent at best. */
+ * link in the meantime the gain is confined to launches with few wavefronts
+ * in flight.  Left alone, the library's own launchers that dirty pages use the
+ * overlapped order when they keep at most 128 wavefronts in flight and the
+ * paper's order otherwise; a mode set here is used as it is. */
 enum { GPUVM_WB_SERIAL = 0, GPUVM_WB_OVERLAPPED = 1 };
 GPUVM_API int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode);
+
+/* One or two hands for the CLOCK policies (GPUVM_POLICY_CLOCK and
+ * _CLOCK_WRITE_AWARE; GPUVM_EINVAL for the others unless spread_eighths is 0).
+ * With one hand (spread_eighths = 0, the textbook second chance) the cursor
+ * clears a set reference bit and passes; since a page is installed with its bit
+ * set, a scan - or any pool whose pages are all in use - makes the cursor go
+ * round once clearing bits before it finds a victim, every position through
+ * the one cursor word.  With two hands (the classical two-handed clock; not in
+ * the paper) a front hand n_frames * spread_eighths / 8 positions (1..7 eighths
+ * of the ring) ahead of the cursor clears the bit of the frame it stands on every time the cursor
+ * advances; the cursor passes a frame only if its page was used again after
+ * the front hand went by.  A new page is safe until the front hand reaches it,
+ * a page that is not used again leaves at the cursor's first visit, and a scan
+ * makes the cursor pass nothing.  The larger the spread, the longer the time
+ * in which a use still counts and the shorter a new page's protection.
+ * Default: two hands half a ring apart (spread_eighths = 4).  Takes effect
+ * with the next launch. */
+#define GPUVM_CLOCK_HANDS_DEFAULT 4
+GPUVM_API int gpuvm_set_clock_hands(gpuvm_t *vm, int spread_eighths);
 
 /* Remote-first reads (off by default; not in the paper, whose every miss
  * migrates the page).  A wavefront of this GPU can read pinned host memory in

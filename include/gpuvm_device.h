@@ -88,16 +88,37 @@
 #define GPUVM_ST_EVICTING 3ull
 #define GPUVM_NO_PAGE 0xFFFFFFFFu
 
-/* slots of one shard of gpuvm_dev_t::stats (order of gpuvm_stats_t) */
+/* slots of one shard of gpuvm_dev_t::stats.  The eight counters a fault
+ * touches come first and share 64 bytes, so that one fault updates them with
+ * ONE atomic instruction (lane r adds to slot r); gpuvm_stats() sorts the
+ * slots into the order of gpuvm_stats_t.  Bytes are not counted per fault:
+ * every page moved is page_bytes long except the last page of the data set if
+ * it is short, whose fetches and write-backs are counted in SHORT_IN / SHORT_OUT.
+ * Evictions are not counted either: a fault takes a frame that was never used
+ * (FRESH, at most n_frames times after a reset) or evicts a victim, so
+ * evictions = faults - fresh, and a fault in the steady state adds to FAULTS only. */
 enum {
-    GPUVM_S_FAULTS = 0, GPUVM_S_EVICTIONS, GPUVM_S_WB_EVICT, GPUVM_S_WB_FLUSH,
-    GPUVM_S_BYTES_IN, GPUVM_S_BYTES_OUT, GPUVM_S_HITS, GPUVM_S_GROUPS,
-    GPUVM_S_COALESCED, GPUVM_S_WAITS, GPUVM_S_SKIPS, GPUVM_S_SWEEPS,
-    GPUVM_S_PHASES, GPUVM_S_NOFETCH, GPUVM_S_REMOTE, GPUVM_S_COUNT = 16
+    GPUVM_S_FAULTS = 0, GPUVM_S_FRESH, GPUVM_S_WB_EVICT, GPUVM_S_SHORT_IN,
+    GPUVM_S_SHORT_OUT, GPUVM_S_SKIPS, GPUVM_S_SWEEPS, GPUVM_S_NOFETCH,
+    GPUVM_S_WB_FLUSH, GPUVM_S_HITS, GPUVM_S_GROUPS, GPUVM_S_COALESCED,
+    GPUVM_S_WAITS, GPUVM_S_PHASES, GPUVM_S_REMOTE, GPUVM_S_COUNT = 16
 };
+#define GPUVM_S_FAULT_SLOTS 8
 
 __device__ __forceinline__ bool gpuvm_uses_ref(unsigned int policy) {
     return policy == GPUVM_POLICY_CLOCK || policy == GPUVM_POLICY_CLOCK_WRITE_AWARE;
+}
+/* Two-handed CLOCK: the frame the front hand stands on while the cursor is on
+ * frame f - n_frames * e / 8 positions ahead, e = 1..7 from the handle's flags;
+ * e = 0 puts it on f itself, which means there is no front hand (one-handed
+ * CLOCK). */
+__device__ __forceinline__ unsigned int gpuvm_clock_spread(const gpuvm_dev_t &vm) {
+    const unsigned int eighths = (vm.flags >> GPUVM_F_HANDS_SHIFT) & GPUVM_F_HANDS_MASK;
+    return gpuvm_uses_ref(vm.policy) ? (unsigned int)(((unsigned long long)vm.n_frames * eighths) >> 3) : 0u;
+}
+__device__ __forceinline__ unsigned int gpuvm_front_hand(const gpuvm_dev_t &vm, unsigned int f) {
+    const unsigned int g = f + gpuvm_clock_spread(vm);
+    return g >= vm.n_frames ? g - vm.n_frames : g;
 }
 /* What a use of a resident page adds to its word: the reference bit under the
  * CLOCK policies; under the generalized CLOCK one step of the use count, which
@@ -172,6 +193,23 @@ GPUVM_DEV unsigned long long *stat_shard(const gpuvm_dev_t &vm) {
 }
 GPUVM_DEV void stat_add(const gpuvm_dev_t &vm, int which, unsigned long long v) {
     __hip_atomic_fetch_add(stat_shard(vm) + which, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+/* the counters of one fault, all at once: the values are wave-uniform, active
+ * lane r adds the r-th of them to slot r of the shard (one instruction for a
+ * full wave; a wave with fewer than eight active lanes takes several turns) */
+GPUVM_DEV void stat_add_fault(const gpuvm_dev_t &vm, unsigned int rank, unsigned int count,
+                              unsigned long long fresh, unsigned long long wb, unsigned long long short_in,
+                              unsigned long long short_out, unsigned long long skips, unsigned long long sweeps,
+                              unsigned long long nofetch) {
+    unsigned long long *shard = stat_shard(vm);
+    for (unsigned int r = rank; r < GPUVM_S_FAULT_SLOTS; r += count) {
+        const unsigned long long v = r == GPUVM_S_FAULTS ? 1ull : r == GPUVM_S_FRESH ? fresh
+                                   : r == GPUVM_S_WB_EVICT ? wb : r == GPUVM_S_SHORT_IN ? short_in
+                                   : r == GPUVM_S_SHORT_OUT ? short_out : r == GPUVM_S_SKIPS ? skips
+                                   : r == GPUVM_S_SWEEPS ? sweeps : nofetch;
+        if (v) __hip_atomic_fetch_add(shard + r, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 /* first error wins; every bounded wait polls this word so that one wave that
@@ -289,72 +327,119 @@ GPUVM_DEV bool touch_in_place(const gpuvm_dev_t &vm, unsigned int page) {
     return false;
 }
 
+/* The cursor stands on frame f, whose owner entry read q and whose page word
+ * read pq: take the frame if the policy allows (true: victim / wb are set, the
+ * victim's word is claimed), else pass it (false).  A clean victim becomes
+ * INVALID with the claiming CAS itself - its frame holds nothing that host
+ * memory does not, and the frame table keeps naming it until the new owner is
+ * recorded, which makes the frame look busy to anybody else; a dirty victim
+ * becomes EVICTING and turns INVALID once its write-back has completed. */
+GPUVM_DEV bool claim_or_pass(const gpuvm_dev_t &vm, unsigned int f, unsigned int q, unsigned long long pq,
+                             unsigned int &victim, unsigned int &wb, unsigned int &skips, unsigned int &sweeps,
+                             bool &redraw, bool &waiting) {
+    if (q == GPUVM_NO_PAGE ||                                  /* first install still under way */
+        ((pq & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT ||
+        (unsigned int)(pq >> GPUVM_PTE_FRAME_SHIFT) != f ||
+        (pq & GPUVM_PTE_PIN_MASK) != 0) {                      /* busy or in use */
+        if (vm.policy == GPUVM_POLICY_FIFO_WAIT) {             /* the paper's rule: wait for this frame */
+            if (!waiting) { waiting = true; stat_add(vm, GPUVM_S_WAITS, 1); }
+            redraw = false;
+            __builtin_amdgcn_s_sleep(4);
+        } else {
+            ++skips;                                           /* this build's default: pass it over */
+        }
+        return false;
+    }
+    if (gpuvm_uses_ref(vm.policy) && (pq & GPUVM_PTE_REF)) {
+        a_and(vm.pte + q, ~GPUVM_PTE_REF);                    /* second chance */
+        ++sweeps;
+        return false;
+    }
+    if (vm.policy == GPUVM_POLICY_GCLOCK && (pq & (GPUVM_PTE_REF | GPUVM_PTE_DEFER))) {
+        a_and(vm.pte + q, ~((pq & GPUVM_PTE_DEFER) ? GPUVM_PTE_DEFER : GPUVM_PTE_REF));   /* count - 1 */
+        ++sweeps;
+        return false;
+    }
+    if (vm.policy == GPUVM_POLICY_CLOCK_WRITE_AWARE && (pq & GPUVM_PTE_DIRTY) && !(pq & GPUVM_PTE_DEFER)) {
+        /* a written page costs a write-back: spare it once and look for a
+         * clean victim first (a CAS: without a pin the page may leave) */
+        unsigned long long expect = pq;
+        a_cas(vm.pte + q, &expect, pq | GPUVM_PTE_DEFER);
+        ++sweeps;
+        return false;
+    }
+    /* claim the victim; fails if anybody pinned it in the meantime */
+    const bool dirty = (pq & GPUVM_PTE_DIRTY) != 0;
+    if (!a_cas(vm.pte + q, &pq, dirty ? pq | GPUVM_PTE_STATE_MASK : pq & GPUVM_PTE_KEEP_MASK)) {
+        if (vm.policy == GPUVM_POLICY_FIFO_WAIT) redraw = false; else ++skips;
+        return false;
+    }
+    victim = q;
+    wb = dirty ? 1u : 0u;
+    return true;
+}
+
 /* Frame allocation + eviction + migration for `page`, whose state word this
  * wave has just moved INVALID -> LOADING.  Returns the frame, or GPUVM_NO_PAGE
- * if a bounded wait ran out (error recorded). */
+ * if a bounded wait ran out (error recorded).
+ * Atomics of one fault on the leader's dependent chain: the ticket, the claim
+ * of the victim; off the chain (nobody waits for their result): the front
+ * hand's bit clearing, the victim's INVALID (dirty victims only - a clean one
+ * becomes INVALID with the claim itself), the publishing xor, the counters. */
 GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool write, unsigned int gen,
-                             const wave_t &w, bool fetch = true) {
-    unsigned int f = 0, victim = GPUVM_NO_PAGE, wb = 0, ok = 1;
+                             const wave_t &w, bool fetch = true, unsigned long long *deferred = nullptr) {
+    unsigned int f = 0, victim = GPUVM_NO_PAGE, wb = 0, ok = 1, n_skips = 0, n_sweeps = 0;
     if (w.leader) {
-        unsigned long long skips = 0, sweeps = 0;
+        unsigned int skips = 0, sweeps = 0;
         bool redraw = true, waiting = false;
         const unsigned long long budget = 8ull * vm.n_frames + vm.spin_limit;
+        /* what the frame after the cursor's looked like when the cursor's own was read:
+         * if this frame is passed and the next ticket is the next frame (nobody else
+         * drew in between), the pass costs the ticket's round trip only */
+        unsigned long long ahead_ticket = ~0ull, ahead_pq = 0;
+        unsigned int ahead_q = GPUVM_NO_PAGE;
         for (unsigned long long tries = 0;; ++tries) {
             if (tries > budget || ((tries & 1023) == 1023 && aborted(vm))) {
                 raise_error(vm, GPUVM_EDEADLK);
                 ok = 0;
                 break;
             }
+            unsigned int q, qg = GPUVM_NO_PAGE, g = f;
             if (redraw) {
                 const unsigned long long t = a_add(vm.hand, 1ull);
                 f = (unsigned int)(t % vm.n_frames);
-                if (t < vm.n_frames) break;                   /* first turn: frame never used */
-            }
-            redraw = true;
-            const unsigned int q = a_load(vm.frame_owner + f);
-            unsigned long long pq = q == GPUVM_NO_PAGE ? 0ull : a_load(vm.pte + q);
-            if (q == GPUVM_NO_PAGE ||                          /* first install still under way */
-                ((pq & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_RESIDENT ||
-                (unsigned int)(pq >> GPUVM_PTE_FRAME_SHIFT) != f ||
-                (pq & GPUVM_PTE_PIN_MASK) != 0) {              /* busy or in use */
-                if (vm.policy == GPUVM_POLICY_FIFO_WAIT) {     /* the paper's rule: wait for this frame */
-                    if (!waiting) { waiting = true; stat_add(vm, GPUVM_S_WAITS, 1); }
-                    redraw = false;
-                    __builtin_amdgcn_s_sleep(4);
-                } else {
-                    ++skips;                                   /* this build's default: pass it over */
+                /* the two hands move together: the frame-table entries are read at once
+                 * (cursor, the frame after it, front hand), then their pages' words */
+                g = gpuvm_front_hand(vm, f);
+                const bool first_turn = t < vm.n_frames;
+                const bool known = t == ahead_ticket;
+                const unsigned int f1 = f + 1 == vm.n_frames ? 0u : f + 1;
+                q = first_turn ? GPUVM_NO_PAGE : known ? ahead_q : a_load(vm.frame_owner + f);
+                const unsigned int q1 = t + 1 < vm.n_frames ? GPUVM_NO_PAGE : a_load(vm.frame_owner + f1);
+                if (g != f) qg = a_load(vm.frame_owner + g);
+                unsigned long long pg = qg == GPUVM_NO_PAGE ? 0ull : a_load(vm.pte + qg);
+                if (first_turn) {                             /* first turn: frame never used */
+                    if ((pg & GPUVM_PTE_REF) && (unsigned int)(pg >> GPUVM_PTE_FRAME_SHIFT) == g &&
+                        ((pg & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT)
+                        a_and(vm.pte + qg, ~GPUVM_PTE_REF);
+                    break;
                 }
+                unsigned long long pq0 = q == GPUVM_NO_PAGE ? 0ull : known ? ahead_pq : a_load(vm.pte + q);
+                ahead_pq = q1 == GPUVM_NO_PAGE ? 0ull : a_load(vm.pte + q1);
+                ahead_q = q1;
+                ahead_ticket = t + 1;
+                if ((pg & GPUVM_PTE_REF) && (unsigned int)(pg >> GPUVM_PTE_FRAME_SHIFT) == g &&
+                    ((pg & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT)
+                    a_and(vm.pte + qg, ~GPUVM_PTE_REF);       /* front hand: the bit starts its last lap */
+                if (claim_or_pass(vm, f, q, pq0, victim, wb, skips, sweeps, redraw, waiting)) break;
                 continue;
             }
-            if (gpuvm_uses_ref(vm.policy) && (pq & GPUVM_PTE_REF)) {
-                a_and(vm.pte + q, ~GPUVM_PTE_REF);            /* second chance */
-                ++sweeps;
-                continue;
-            }
-            if (vm.policy == GPUVM_POLICY_GCLOCK && (pq & (GPUVM_PTE_REF | GPUVM_PTE_DEFER))) {
-                a_and(vm.pte + q, ~((pq & GPUVM_PTE_DEFER) ? GPUVM_PTE_DEFER : GPUVM_PTE_REF));   /* count - 1 */
-                ++sweeps;
-                continue;
-            }
-            if (vm.policy == GPUVM_POLICY_CLOCK_WRITE_AWARE && (pq & GPUVM_PTE_DIRTY) && !(pq & GPUVM_PTE_DEFER)) {
-                /* a written page costs a write-back: spare it once and look for a
-                 * clean victim first (a CAS: without a pin the page may leave) */
-                unsigned long long expect = pq;
-                a_cas(vm.pte + q, &expect, pq | GPUVM_PTE_DEFER);
-                ++sweeps;
-                continue;
-            }
-            /* claim the victim; fails if anybody pinned it in the meantime */
-            if (!a_cas(vm.pte + q, &pq, pq | GPUVM_PTE_STATE_MASK)) {
-                if (vm.policy == GPUVM_POLICY_FIFO_WAIT) redraw = false; else ++skips;
-                continue;
-            }
-            victim = q;
-            wb = (pq & GPUVM_PTE_DIRTY) ? 1u : 0u;
-            break;
+            redraw = true;                                    /* the waiting policy looks at its frame again */
+            q = a_load(vm.frame_owner + f);
+            const unsigned long long pq = q == GPUVM_NO_PAGE ? 0ull : a_load(vm.pte + q);
+            if (claim_or_pass(vm, f, q, pq, victim, wb, skips, sweeps, redraw, waiting)) break;
         }
-        if (skips) stat_add(vm, GPUVM_S_SKIPS, skips);
-        if (sweeps) stat_add(vm, GPUVM_S_SWEEPS, sweeps);
+        n_skips = skips; n_sweeps = sweeps;
     }
     ok = bcast(ok);
     if (!ok) {
@@ -364,56 +449,69 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
     f = bcast(f); victim = bcast(victim); wb = bcast(wb);
     char *frame = vm.frames + ((size_t)f << vm.page_shift);
     const unsigned int len = page_len(vm, page);
+    const unsigned int full = 1u << vm.page_shift;
+    unsigned int vlen = 0;
     bool fetched = false;
-    if (victim != GPUVM_NO_PAGE) {
-        if (wb) {
-            const unsigned int vlen = page_len(vm, victim);
-            if ((vm.flags & GPUVM_F_OVERLAPPED_WRITEBACK) && fetch && vlen == len && (len & 15u) == 0) {
-                /* write-back and fetch share one pass over the frame */
-                swap_frame_with_host(frame, vm.host + ((size_t)victim << vm.page_shift),
-                                     vm.host + ((size_t)page << vm.page_shift), len, w);
-                fetched = true;
-            } else {
-                copy_frame_to_host(vm.host + ((size_t)victim << vm.page_shift), frame, vlen, w);
-            }
-            wait_vm();                                        /* posted before the victim can be re-read */
-            if (w.leader) { stat_add(vm, GPUVM_S_WB_EVICT, 1); stat_add(vm, GPUVM_S_BYTES_OUT, vlen); }
+    if (wb) {                                                 /* only a dirty victim is still EVICTING here */
+        vlen = page_len(vm, victim);
+        if ((vm.flags & GPUVM_F_OVERLAPPED_WRITEBACK) && fetch && vlen == len && (len & 15u) == 0) {
+            /* write-back and fetch share one pass over the frame */
+            swap_frame_with_host(frame, vm.host + ((size_t)victim << vm.page_shift),
+                                 vm.host + ((size_t)page << vm.page_shift), len, w);
+            fetched = true;
+        } else {
+            copy_frame_to_host(vm.host + ((size_t)victim << vm.page_shift), frame, vlen, w);
         }
-        if (w.leader) {
-            a_and(vm.pte + victim, GPUVM_PTE_KEEP_MASK);      /* INVALID; waiters keep their pins */
-            stat_add(vm, GPUVM_S_EVICTIONS, 1);
-        }
+        wait_vm();                                            /* posted before the victim can be re-read */
+        if (w.leader) a_and(vm.pte + victim, GPUVM_PTE_KEEP_MASK);      /* INVALID; waiters keep their pins */
     }
     if (fetch && !fetched) copy_host_to_frame(frame, vm.host + ((size_t)page << vm.page_shift), len, w);
     if (w.leader) a_store(vm.frame_owner + f, page);
     wait_vm();                                                /* the page is in the frame */
-    if (w.leader) {
-        /* only this wave changes anything but the pin field while the page is
-         * LOADING, so one xor moves state, frame, flags and generation at once */
-        const unsigned long long flip =
-            ((GPUVM_ST_LOADING ^ GPUVM_ST_RESIDENT) << GPUVM_PTE_STATE_SHIFT) |
-            ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) |
-            (vm.policy == GPUVM_POLICY_GCLOCK ? 0ull : GPUVM_PTE_REF) |    /* use count 0 there */
-            (write ? GPUVM_PTE_DIRTY : 0ull) |
-            ((unsigned long long)(gen ^ ((gen + 1u) & 0xFFFu)) << GPUVM_PTE_GEN_SHIFT);
+    /* only this wave changes anything but the pin field while the page is
+     * LOADING, so one xor moves state, frame, flags and generation at once */
+    const unsigned long long flip =
+        ((GPUVM_ST_LOADING ^ GPUVM_ST_RESIDENT) << GPUVM_PTE_STATE_SHIFT) |
+        ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) |
+        (vm.policy == GPUVM_POLICY_GCLOCK ? 0ull : GPUVM_PTE_REF) |        /* use count 0 there */
+        (write ? GPUVM_PTE_DIRTY : 0ull) |
+        ((unsigned long long)(gen ^ ((gen + 1u) & 0xFFFu)) << GPUVM_PTE_GEN_SHIFT);
+    if (deferred) {
+        /* the caller accesses the frame first and then publishes and drops its
+         * reference with ONE add: the bits above the pin field are known exactly
+         * (LOADING, this generation, nothing else), so new - old - 1 is exact */
+        const unsigned long long before = (GPUVM_ST_LOADING << GPUVM_PTE_STATE_SHIFT) |
+                                          ((unsigned long long)gen << GPUVM_PTE_GEN_SHIFT);
+        *deferred = (before ^ flip) - before - 1ull;
+    } else if (w.leader) {
         a_xor(vm.pte + page, flip);                           /* publish: RESIDENT */
-        stat_add(vm, GPUVM_S_FAULTS, 1);
-        if (fetch) stat_add(vm, GPUVM_S_BYTES_IN, len); else stat_add(vm, GPUVM_S_NOFETCH, 1);
     }
+    stat_add_fault(vm, w.rank, w.count, victim == GPUVM_NO_PAGE, wb, fetch && len != full, wb && vlen != full,
+                   bcast(n_skips), bcast(n_sweeps), fetch ? 0u : 1u);
     return f;
 }
 
-/* lookup + pin of one page for the whole wave; see gpuvm_acquire */
-GPUVM_DEV char *acquire_page(const gpuvm_dev_t &vm, unsigned int page_any, bool write, bool fetch) {
+/* lookup + pin of one page for the whole wave; see gpuvm_acquire.  `hint` is
+ * what the caller last read from the page's word, if it has (GPUVM_NO_HINT
+ * otherwise): when that says INVALID, reference count and INVALID -> LOADING
+ * are tried as one CAS on it instead of an add followed by a CAS. */
+#define GPUVM_NO_HINT (~0ull)
+GPUVM_DEV char *acquire_page(const gpuvm_dev_t &vm, unsigned int page_any, bool write, bool fetch,
+                             unsigned long long hint = GPUVM_NO_HINT, unsigned long long *deferred = nullptr) {
     const wave_t w = wave_now();
     const unsigned int page = bcast(page_any);
     unsigned long long *pte = vm.pte + page;
     unsigned long long cur = 0;
     unsigned int how = 0;                     /* 0 hit, 1 this wave faults, 2 gave up */
     if (w.leader) {
-        cur = a_add(pte, 1ull) + 1ull;        /* lookup and reference count in one atomic */
+        if (hint != GPUVM_NO_HINT && ((hint & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_INVALID) {
+            cur = hint;
+            const unsigned long long mine = ((hint & GPUVM_PTE_KEEP_MASK) + 1ull) | (GPUVM_ST_LOADING << GPUVM_PTE_STATE_SHIFT);
+            if (a_cas(pte, &cur, mine)) { cur = mine; how = 1; }
+        }
+        if (how == 0) cur = a_add(pte, 1ull) + 1ull;        /* lookup and reference count in one atomic */
         unsigned int spins = 0;
-        for (;;) {
+        while (how == 0) {
             const unsigned long long st = (cur & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT;
             if (st == GPUVM_ST_RESIDENT) break;
             if (st == GPUVM_ST_INVALID) {     /* inter-wave arbitration: one wave locks the entry */
@@ -433,12 +531,12 @@ GPUVM_DEV char *acquire_page(const gpuvm_dev_t &vm, unsigned int page_any, bool 
     }
     how = bcast(how);
     if (how == 2) return vm.frames;
+    cur = bcast(cur);
     unsigned int f;
     if (how == 1) {
-        f = fault(vm, page, write, (unsigned int)(cur >> GPUVM_PTE_GEN_SHIFT) & 0xFFFu, w, fetch);
-        if (f == GPUVM_NO_PAGE) return vm.frames;
+        f = fault(vm, page, write, (unsigned int)(cur >> GPUVM_PTE_GEN_SHIFT) & 0xFFFu, w, fetch, deferred);
+        if (f == GPUVM_NO_PAGE) { if (deferred) *deferred = 0; return vm.frames; }
     } else {
-        cur = bcast(cur);
         f = (unsigned int)(cur >> GPUVM_PTE_FRAME_SHIFT);
         if (w.leader) {
             unsigned long long need = 0;
@@ -603,12 +701,16 @@ GPUVM_DEV bool optimistic_read_stands(const gpuvm_dev_t &vm, unsigned int page, 
 struct no_remote {};      /* tag: this access has no in-place form (writes, atomics) */
 template <typename T, typename Op, typename Remote>
 GPUVM_DEV void access_missing(const gpuvm_dev_t &vm, unsigned int page, unsigned int off, bool write, bool pending,
-                              Op op, Remote remote) {
+                              unsigned long long word, Op op, Remote remote) {
     for (;;) {
         const unsigned long long todo = __builtin_amdgcn_ballot_w64(pending);
         if (todo == 0) break;
         const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
         const unsigned int group_page = __builtin_amdgcn_readlane(page, first);
+        /* what the group's first lane last saw in the page's word (the hit pass read it) */
+        const unsigned long long hint =
+            ((unsigned long long)(unsigned int)__builtin_amdgcn_readlane((unsigned int)(word >> 32), first) << 32) |
+            (unsigned int)__builtin_amdgcn_readlane((unsigned int)word, first);
         if constexpr (!__is_same(Remote, no_remote)) {
             /* remote-first: the group's first lane asks whether the page has earned
              * its migration yet; if not, the lanes read host memory in place */
@@ -625,12 +727,16 @@ GPUVM_DEV void access_missing(const gpuvm_dev_t &vm, unsigned int page, unsigned
                 }
             }
         }
-        char *frame = gpuvm_acquire(vm, group_page, write);
+        /* a page this wave faults in is published only after the group's lanes have
+         * had their access: publishing and dropping the reference are one atomic */
+        unsigned long long publish = 0;
+        char *frame = acquire_page(vm, group_page, write, true, hint, &publish);
         if (pending && page == group_page) {
             op(reinterpret_cast<T *>(frame + off));
             pending = false;
         }
-        gpuvm_release(vm, group_page);
+        wait_vm();
+        if (wave_now().leader) a_add(vm.pte + group_page, publish ? publish : ~0ull);
     }
 }
 
@@ -673,6 +779,7 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
     const unsigned int lane = __lane_id();
     bool resident;
     unsigned int n_groups = 0;
+    unsigned long long seen = 0;              /* the page's word as this lane last saw it, without a pin of ours */
 
     if (!write) {
         /* hit pass, reads.  One page for the whole wave (unit stride, a row
@@ -700,9 +807,10 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
         if (resident)
             op(reinterpret_cast<T *>(vm.frames + ((size_t)(word >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off));
         wait_vm();
+        seen = word;
         if (__builtin_amdgcn_ballot_w64(resident)) {
             const unsigned long long again = load_word();
-            if (resident) resident = optimistic_read_stands(vm, page, word, again, !one_page || lane == first);
+            if (resident) { resident = optimistic_read_stands(vm, page, word, again, !one_page || lane == first); seen = again; }
         }
     } else {
         /* hit pass, writes: group the wanting lanes by page (leader_lane = lowest
@@ -740,6 +848,7 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
             }
             a_add(vm.pte + page, ~0ull);                      /* unpin, or give the pin back */
         }
+        seen = word;                          /* before our pin = after we gave it back, unless somebody else came by */
     }
     if (vm.flags & GPUVM_F_ACCESS_STATS) {
         /* pages, not lanes: a page with any lane still missing counts as a miss */
@@ -752,7 +861,7 @@ __device__ __forceinline__ void gpuvm_access(const gpuvm_dev_t &vm, unsigned lon
             stat_add(vm, GPUVM_S_HITS, n_groups - n_missing);
         }
     }
-    access_missing<T>(vm, page, off, write, want && !resident, op, remote);
+    access_missing<T>(vm, page, off, write, want && !resident, seen, op, remote);
 }
 
 /* Elements are 4 or 8 bytes wide and are read, written and updated with

@@ -70,6 +70,7 @@ _SIGNATURES = {
     "gpuvm_device_handle": ([C.c_void_p, C.POINTER(Dev)], C.c_int),
     "gpuvm_configure": ([C.c_void_p, C.c_uint32, C.c_int], C.c_int),
     "gpuvm_set_writeback_mode": ([C.c_void_p, C.c_int], C.c_int),
+    "gpuvm_set_clock_hands": ([C.c_void_p, C.c_int], C.c_int),
     "gpuvm_set_remote_first": ([C.c_void_p, C.c_size_t], C.c_int),
     "gpuvm_set_waves_per_cu": ([C.c_void_p, C.c_int], C.c_int),
     "gpuvm_check": ([C.c_void_p, C.c_void_p], C.c_int),
@@ -187,6 +188,18 @@ def gpuvm_configure(vm, spin_limit=0, access_stats=False):
 
 def gpuvm_set_writeback_mode(vm, mode):
     _call("gpuvm_set_writeback_mode", vm, mode)
+
+
+def gpuvm_set_clock_hands(vm, spread_eighths):
+    _call("gpuvm_set_clock_hands", vm, spread_eighths)
+
+
+def clock_spread(vm):
+    """Frames between the front hand and the cursor on this handle (0 = one hand)."""
+    d = gpuvm_device_handle(vm)
+    eighths = (d.flags >> 2) & 7
+    uses_bit = d.policy in (POLICY_CLOCK, POLICY_CLOCK_WRITE_AWARE)
+    return (d.n_frames * eighths) >> 3 if uses_bit else 0
 
 
 def gpuvm_set_remote_first(vm, bytes_per_touch):

@@ -28,6 +28,7 @@ struct gpuvm {
     int cus;
     int waves_per_cu;
     bool waves_chosen;            // set by the caller (or the environment): launchers do not second-guess it
+    bool wb_chosen = false;       // write-back order set by the caller: launchers do not second-guess it
     size_t page_bytes;
     // deterministic mode scratch (allocated on first use)
     unsigned int *stamp = nullptr;        // [n_pages] phase tag of the last toucher
@@ -58,6 +59,7 @@ int check_kernel_error(gpuvm_t *vm);      // reads the error word a kernel may h
 int grid_for_waves(int waves);            // workgroups for that many wavefronts
 int launch_waves(const gpuvm_t *vm, size_t work_waves);          // waves to keep in flight; 0 = pool too small
 int launch_waves_duplex(const gpuvm_t *vm, size_t work_waves);   // the same for launches that write back as much as they fetch
+gpuvm_dev_t dev_for_writers(const gpuvm_t *vm, int waves);       // device view for a launch that dirties pages, with `waves` in flight
 
 // Fill kernels (a copy per translation unit; used instead of hipMemsetAsync so
 // that a caller may capture the launchers in a graph).

@@ -64,8 +64,10 @@ __global__ __launch_bounds__(1024) void k_phase_assign(gpuvm_dev_t vm, const uns
             if (++guard > 3ull * vm.n_frames + 3) { raise_error(vm, GPUVM_EDEADLK); goto out; }
             f = (unsigned int)(hand % vm.n_frames);
             ++hand;
+            const unsigned int g = gpuvm_front_hand(vm, f);           // two-handed CLOCK: the front hand moves with the cursor
+            if (g != f && vm.frame_owner[g] != GPUVM_NO_PAGE) vm.pte[vm.frame_owner[g]] &= ~GPUVM_PTE_REF;
             const unsigned int q = vm.frame_owner[f];
-            if (q == GPUVM_NO_PAGE) break;
+            if (q == GPUVM_NO_PAGE) { st[GPUVM_S_FRESH] += 1; break; }
             const unsigned long long pq = vm.pte[q];
             if (pq & GPUVM_PTE_PIN_MASK) { st[GPUVM_S_SKIPS] += 1; continue; }
             if (gpuvm_uses_ref(vm.policy) && (pq & GPUVM_PTE_REF)) {
@@ -85,8 +87,7 @@ __global__ __launch_bounds__(1024) void k_phase_assign(gpuvm_dev_t vm, const uns
             }
             victim = q;
             wb = (pq & GPUVM_PTE_DIRTY) ? 1u : 0u;
-            st[GPUVM_S_EVICTIONS] += 1;
-            if (wb) { st[GPUVM_S_WB_EVICT] += 1; st[GPUVM_S_BYTES_OUT] += page_len(vm, q); }
+            if (wb) { st[GPUVM_S_WB_EVICT] += 1; st[GPUVM_S_SHORT_OUT] += page_len(vm, q) != (1u << vm.page_shift); }
             vm.pte[q] = pq & GPUVM_PTE_GEN_MASK;                      // INVALID
             break;
         }
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(1024) void k_phase_assign(gpuvm_dev_t vm, const uns
                     ((vm.pte[p] + (1ull << GPUVM_PTE_GEN_SHIFT)) & GPUVM_PTE_GEN_MASK) |
                     1ull;                                             // next generation, pinned once
         st[GPUVM_S_FAULTS] += 1;
-        st[GPUVM_S_BYTES_IN] += page_len(vm, p);
+        st[GPUVM_S_SHORT_IN] += page_len(vm, p) != (1u << vm.page_shift);
         jobs[done].page = p; jobs[done].frame = f; jobs[done].victim = victim; jobs[done].writeback = wb;
         ++done;
     }

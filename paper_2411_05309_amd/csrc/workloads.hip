@@ -451,7 +451,7 @@ int gpuvm_run_scatter_increment_masked(gpuvm_t *vm, const uint32_t *d_idx, const
     if (n == 0) return GPUVM_OK;
     const int waves = launch_waves_duplex(vm, (n + 63) / 64);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
-    k_scatter_inc_masked<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, d_mask, n,
+    k_scatter_inc_masked<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(dev_for_writers(vm, waves), d_idx, d_mask, n,
                                                                                      vm->dev.bytes / 8);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
@@ -462,7 +462,7 @@ int gpuvm_run_scatter_increment(gpuvm_t *vm, const uint32_t *d_idx, size_t n, vo
     if (n == 0) return GPUVM_OK;
     const int waves = launch_waves_duplex(vm, (n + 63) / 64);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
-    k_scatter_inc<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, vm->dev.bytes / 8);
+    k_scatter_inc<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(dev_for_writers(vm, waves), d_idx, n, vm->dev.bytes / 8);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }
@@ -478,9 +478,9 @@ static int run_vector_add(gpuvm_t *vm_a, gpuvm_t *vm_b, gpuvm_t *vm_c, size_t n,
     const int waves = std::min({launch_waves(vm_a, work), launch_waves(vm_b, work), launch_waves(vm_c, work)});
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
     if (overwrite)
-        k_vector_add<true><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, vm_c->dev, n);
+        k_vector_add<true><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, dev_for_writers(vm_c, waves), n);
     else
-        k_vector_add<false><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, vm_c->dev, n);
+        k_vector_add<false><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm_a->dev, vm_b->dev, dev_for_writers(vm_c, waves), n);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }
@@ -572,7 +572,18 @@ static int run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x,
     const unsigned int skew = (unsigned int)std::max<size_t>(1, std::min<size_t>({(size_t)64, rows_in_pool / 4, rows}));
     // one pass over the rows per wave is what the window reasons about
     const bool single_pass = (size_t)waves * 64 >= cols;
-    const unsigned int window = single_pass && rows_in_pool >= 16 ? (unsigned int)std::min<size_t>(rows_in_pool / 2, 0x7FFFFFFF) : 0;
+    // Under the two-handed CLOCK a page keeps its first reference bit for the part of
+    // the ring the front hand has not covered yet, (8 - e) / 8 of it; a page that is
+    // still being used after that is marked again and outlives its turn by a whole
+    // lap, dead weight that the rows in flight then lack.  So every use of a page -
+    // from the helper that brings it in to the slowest wave, window + window / 2 rows
+    // later - has to fall inside that part: window = 2/3 of it, rounded down to a
+    // quarter of the pool for the default half-ring spread.  One hand, FIFO and the
+    // generalized CLOCK keep half the pool.
+    const unsigned int eighths = (vm->dev.flags >> GPUVM_F_HANDS_SHIFT) & GPUVM_F_HANDS_MASK;
+    const bool two_hands = eighths && (vm->dev.policy == GPUVM_POLICY_CLOCK || vm->dev.policy == GPUVM_POLICY_CLOCK_WRITE_AWARE);
+    const size_t lead = two_hands ? rows_in_pool * (8 - eighths) / 16 : rows_in_pool / 2;
+    const unsigned int window = single_pass && rows_in_pool >= 16 ? (unsigned int)std::min<size_t>(std::max<size_t>(lead, 4), 0x7FFFFFFF) : 0;
     // fault-ahead helpers: what is left of the wave budget, at most two per compute unit
     const int helpers = window ? std::min(cap - waves, vm->cus * 2) / kWavesPerBlock * kWavesPerBlock : 0;
     hipStream_t s = (hipStream_t)stream;

@@ -10,7 +10,7 @@
 // and after writing the dirty frames back the host array holds exactly
 // initial value + number of increments, and the last stored values.
 //
-// usage: driver policy threads frames page_bytes pages ops_per_thread seed writeback_mode yield_every remote_touches
+// usage: driver policy threads frames page_bytes pages ops_per_thread seed writeback_mode yield_every remote_touches clock_hands
 #include "shim.h"
 #include GPUVM_DEVICE_HEADER
 
@@ -37,13 +37,14 @@ struct rng_t {
 };
 
 int main(int argc, char **argv) {
-    if (argc != 11) { fprintf(stderr, "usage: see the head of driver.cpp\n"); return 2; }
+    if (argc != 12) { fprintf(stderr, "usage: see the head of driver.cpp\n"); return 2; }
     const unsigned policy = atoi(argv[1]), threads = atoi(argv[2]), frames = atoi(argv[3]);
     const unsigned page_bytes = atoi(argv[4]), pages = atoi(argv[5]), ops = atoi(argv[6]);
     const u64 seed = strtoull(argv[7], nullptr, 10);
     const unsigned wb_mode = atoi(argv[8]);
     shim_yield_every = atoi(argv[9]);
     const unsigned remote_touches = atoi(argv[10]);         // 0: every miss migrates; else reads in place before migration
+    const unsigned clock_hands = atoi(argv[11]) & GPUVM_F_HANDS_MASK;   // CLOCK policies: front hand this many eighths of the ring ahead, 0 = one hand
     if (frames < 2 * threads || frames < 8) { fprintf(stderr, "need frames >= max(8, 2 * threads)\n"); return 2; }
 
     const u64 per_page = page_bytes / 8;
@@ -61,7 +62,7 @@ int main(int argc, char **argv) {
     vm.pte = pte.data(); vm.frame_owner = owner.data(); vm.hand = hand.data(); vm.stats = stats.data();
     vm.frames = pool.data(); vm.host = (char *)host.data();
     vm.bytes = n_shared * 8; vm.n_pages = pages; vm.n_frames = frames; vm.page_shift = shift;
-    vm.policy = policy; vm.spin_limit = 1u << 30; vm.flags = (wb_mode ? GPUVM_F_OVERLAPPED_WRITEBACK : 0) | (remote_touches << GPUVM_F_REMOTE_SHIFT);
+    vm.policy = policy; vm.spin_limit = 1u << 30; vm.flags = (wb_mode ? GPUVM_F_OVERLAPPED_WRITEBACK : 0) | (remote_touches << GPUVM_F_REMOTE_SHIFT) | (clock_hands << GPUVM_F_HANDS_SHIFT);
 
     // element i is private to thread t if i % stride == t (t < threads) and i / stride < priv
     const u64 stride = n_shared / priv;
@@ -156,7 +157,7 @@ int main(int argc, char **argv) {
     u64 tot[GPUVM_S_COUNT] = {0};
     for (int s = 0; s < GPUVM_STAT_SLOTS; ++s)
         for (int c = 0; c < GPUVM_S_COUNT; ++c) tot[c] += stats[(size_t)s * GPUVM_S_COUNT + c];
-    if (tot[GPUVM_S_FAULTS] - tot[GPUVM_S_EVICTIONS] != resident) fail("faults - evictions != resident", tot[GPUVM_S_FAULTS], tot[GPUVM_S_EVICTIONS], resident);
+    if (tot[GPUVM_S_FAULTS] - (tot[GPUVM_S_FAULTS] - tot[GPUVM_S_FRESH]) != resident) fail("faults - evictions != resident", tot[GPUVM_S_FAULTS], (tot[GPUVM_S_FAULTS] - tot[GPUVM_S_FRESH]), resident);
     u64 incs = 0;
     for (u64 i = 0; i < n_shared; ++i) {
         const int o = owner_of(i);
@@ -167,7 +168,7 @@ int main(int argc, char **argv) {
     printf("{\"failures\": %d, \"faults\": %llu, \"evictions\": %llu, \"writebacks_evict\": %llu, \"loading_waits\": %llu, "
            "\"alloc_skips\": %llu, \"alloc_sweeps\": %llu, \"resident\": %llu, \"dirty_at_end\": %llu, \"increments\": %llu, "
            "\"remote_reads\": %llu}\n",
-           failures.load(), tot[GPUVM_S_FAULTS], tot[GPUVM_S_EVICTIONS], tot[GPUVM_S_WB_EVICT], tot[GPUVM_S_WAITS],
+           failures.load(), tot[GPUVM_S_FAULTS], (tot[GPUVM_S_FAULTS] - tot[GPUVM_S_FRESH]), tot[GPUVM_S_WB_EVICT], tot[GPUVM_S_WAITS],
            tot[GPUVM_S_SKIPS], tot[GPUVM_S_SWEEPS], resident, dirty, incs, tot[GPUVM_S_REMOTE]);
     return failures.load() ? 1 : 0;
 }

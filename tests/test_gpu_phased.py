@@ -17,6 +17,26 @@ _POL = {gv.POLICY_FIFO: oracle.FIFO, gv.POLICY_CLOCK: oracle.CLOCK, gv.POLICY_CL
         gv.POLICY_GCLOCK: oracle.GCLOCK}
 
 
+# (policy, hands): hands = e puts the CLOCK policies' front hand frames * e / 8 ahead of the cursor, 0 = one hand
+_CASES = [(gv.POLICY_CLOCK, 4), (gv.POLICY_CLOCK, 0), (gv.POLICY_CLOCK, 7), (gv.POLICY_CLOCK, 1), (gv.POLICY_FIFO, 0),
+          (gv.POLICY_GCLOCK, 0)]
+_CASES_W = _CASES + [(gv.POLICY_CLOCK_WRITE_AWARE, 4), (gv.POLICY_CLOCK_WRITE_AWARE, 0)]
+
+
+def _spread(policy, frames, hands):
+    return frames * hands // 8 if policy in (gv.POLICY_CLOCK, gv.POLICY_CLOCK_WRITE_AWARE) else 0
+
+
+def _set_hands(b, policy, frames, hands):
+    if policy in (gv.POLICY_CLOCK, gv.POLICY_CLOCK_WRITE_AWARE):
+        if hands != 4:
+            gv.gpuvm_set_clock_hands(b.vm, hands)              # 4 is the default
+    else:
+        with pytest.raises(gv.GpuvmError):
+            gv.gpuvm_set_clock_hands(b.vm, 4)                  # no reference bit, no front hand
+    assert gv.clock_spread(b.vm) == _spread(policy, frames, hands)
+
+
 def _compare_with_replay(b, sim, frames):
     st, f, owner, hand = check_invariants(b, read_only=False)
     c = sim.counters
@@ -36,22 +56,23 @@ def _compare_with_replay(b, sim, frames):
     return st
 
 
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_GCLOCK])
+@pytest.mark.parametrize("policy,hands", _CASES)
 @pytest.mark.parametrize("n_elems,page,frames,n_idx,phase_len", [
     (1 << 18, 4096, 64, 20000, 48),        # 256 pages over 64 frames, phases pin most of the pool
     ((1 << 16) + 100, 4096, 16, 5003, 7),  # short last page, ragged last phase
     (1 << 16, 4096, 128, 4000, 64),        # fits
     (1 << 20, 4096, 256, 30000, 200),
 ])
-def test_gather_phased_equals_sequential_replay(gpu, policy, n_elems, page, frames, n_idx, phase_len):
+def test_gather_phased_equals_sequential_replay(gpu, policy, hands, n_elems, page, frames, n_idx, phase_len):
     data = inputs.u32_values(1, 0, n_elems)
     # skewed indices so that CLOCK and FIFO differ and pinned frames are passed over
     r = inputs.zipf_ranks(4, 0, n_idx, n_elems, 1.2) - 1
     idx = ((r * 2654435761) % n_elems).astype(np.uint32)
     want, want_sum = oracle.gather(data, idx)
-    sim = oracle.PagingSim(page // 8, frames, _POL[policy], n_words=-(-data.nbytes // 8))
+    sim = oracle.PagingSim(page // 8, frames, _POL[policy], n_words=-(-data.nbytes // 8), spread=_spread(policy, frames, hands))
     sim.run((idx.astype(np.uint64) * 4) // 8, phase_len=phase_len)
     with Backing(data, page, frames * page, policy) as b:
+        _set_hands(b, policy, frames, hands)
         d_idx = dev(idx)
         d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
         d_sum = torch.zeros(1, dtype=torch.int64, device="cuda")
@@ -63,8 +84,8 @@ def test_gather_phased_equals_sequential_replay(gpu, policy, n_elems, page, fram
         assert np.array_equal(b.arr, data)
 
 
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_GCLOCK])
-def test_embedding_shaped_page_sequence_equals_sequential_replay(gpu, policy):
+@pytest.mark.parametrize("policy,hands", _CASES)
+def test_embedding_shaped_page_sequence_equals_sequential_replay(gpu, policy, hands):
     """The embedding-bag configuration at reduced scale in deterministic mode: the
     page sequence of its row reads (scrambled Zipf(1.05) ids, 512-byte rows, 128
     rows per 64 KiB page, pool a quarter of the table, one bag of 32 rows per
@@ -77,9 +98,10 @@ def test_embedding_shaped_page_sequence_equals_sequential_replay(gpu, policy):
     idx = (ids.astype(np.uint64) * dim).astype(np.uint32)                   # first word of each row
     data = table.view(np.uint32)
     want, want_sum = oracle.gather(data, idx)
-    sim = oracle.PagingSim(page // 8, frames, _POL[policy], n_words=-(-data.nbytes // 8))
+    sim = oracle.PagingSim(page // 8, frames, _POL[policy], n_words=-(-data.nbytes // 8), spread=_spread(policy, frames, hands))
     sim.run((idx.astype(np.uint64) * 4) // 8, phase_len=bag_len)
     with Backing(data, page, frames * page, policy) as b:
+        _set_hands(b, policy, frames, hands)
         d_out = torch.zeros(idx.size, dtype=torch.int32, device="cuda")
         gv.gpuvm_run_gather_phased(b.vm, dev(idx), idx.size, bag_len, d_out, None)
         assert np.array_equal(host(d_out, np.uint32), want)
@@ -88,18 +110,19 @@ def test_embedding_shaped_page_sequence_equals_sequential_replay(gpu, policy):
 
 
 @pytest.mark.parametrize("wb_mode", [gv.WB_OVERLAPPED, gv.WB_SERIAL])
-@pytest.mark.parametrize("policy", [gv.POLICY_CLOCK, gv.POLICY_FIFO, gv.POLICY_CLOCK_WRITE_AWARE, gv.POLICY_GCLOCK])
+@pytest.mark.parametrize("policy,hands", _CASES_W)
 @pytest.mark.parametrize("n_elems,page,frames,n_upd,phase_len", [
     (1 << 15, 4096, 16, 20000, 12),
     ((1 << 14) + 9, 4096, 8, 6001, 5),
 ])
-def test_scatter_phased_equals_sequential_replay(gpu, policy, n_elems, page, frames, n_upd, phase_len, wb_mode):
+def test_scatter_phased_equals_sequential_replay(gpu, policy, hands, n_elems, page, frames, n_upd, phase_len, wb_mode):
     r = inputs.zipf_ranks(6, 0, n_upd, n_elems, 0.9) - 1
     idx = ((r * 40503) % n_elems).astype(np.uint32)
     want = np.zeros(n_elems, np.uint64)
-    sim = oracle.PagingSim(page // 8, frames, _POL[policy], host=want)
+    sim = oracle.PagingSim(page // 8, frames, _POL[policy], host=want, spread=_spread(policy, frames, hands))
     sim.run(idx.astype(np.uint64), op=oracle.ADD, val=1, phase_len=phase_len)
     with Backing(np.zeros(n_elems, np.uint64), page, frames * page, policy) as b:
+        _set_hands(b, policy, frames, hands)
         gv.gpuvm_set_writeback_mode(b.vm, wb_mode)
         gv.gpuvm_run_scatter_increment_phased(b.vm, dev(idx), n_upd, phase_len)
         st = _compare_with_replay(b, sim, frames)
@@ -164,11 +187,12 @@ def test_gather_phased_full_size_config(gpu):
     data = inputs.u32_values(0x9E3779B9, 0, n_elems)
     idx = inputs.u32_indices(1, 0, n_idx, n_elems)
     want, want_sum = oracle.gather(data, idx)
-    sim = oracle.PagingSim(page // 8, frames, oracle.CLOCK, n_words=data.nbytes // 8)
+    sim = oracle.PagingSim(page // 8, frames, oracle.CLOCK, n_words=data.nbytes // 8, spread=frames // 2)   # the default: two hands
     sim.run((idx.astype(np.uint64) * 4) // 8, phase_len=phase_len)
     # independent-reference sanity: ~3/4 of the distinct pages of a phase miss
     assert 0.7 * n_idx < sim.counters["faults"] < 0.8 * n_idx
     with Backing(data, page, frames * page, gv.POLICY_CLOCK) as b:
+        assert gv.clock_spread(b.vm) == frames // 2
         d_out = torch.zeros(n_idx, dtype=torch.int32, device="cuda")
         d_sum = torch.zeros(1, dtype=torch.int64, device="cuda")
         gv.gpuvm_run_gather_phased(b.vm, dev(idx), n_idx, phase_len, d_out, d_sum)

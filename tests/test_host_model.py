@@ -41,19 +41,19 @@ def driver(tmp_path_factory):
 POLICIES = {"fifo": 0, "clock": 1, "fifo_wait": 2, "clock_write_aware": 3, "gclock": 4}
 
 
-@pytest.mark.parametrize("wb_mode,remote_touches", [(0, 0), (1, 0), (0, 3), (0, 40)])
+@pytest.mark.parametrize("wb_mode,remote_touches,hands", [(0, 0, 4), (1, 0, 4), (0, 3, 4), (0, 40, 0), (0, 0, 0), (1, 0, 7)])
 @pytest.mark.parametrize("policy", sorted(POLICIES))
 @pytest.mark.parametrize("threads,frames,page,pages,ops,yield_every", [
     (6, 12, 4096, 40, 6000, 7),        # more threads than cores' worth of luck: yields inside the page copies
     (4, 8, 4096, 64, 8000, 0),         # the smallest pool the launchers accept
     (8, 24, 8192, 48, 4000, 3),
 ])
-def test_fault_protocol_under_host_threads(driver, policy, wb_mode, remote_touches, threads, frames, page, pages, ops,
-                                           yield_every):
+def test_fault_protocol_under_host_threads(driver, policy, wb_mode, remote_touches, hands, threads, frames, page, pages,
+                                           ops, yield_every):
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
     for seed in (1, 2):
         r = subprocess.run([driver, str(POLICIES[policy]), str(threads), str(frames), str(page), str(pages), str(ops),
-                            str(seed), str(wb_mode), str(yield_every), str(remote_touches)],
+                            str(seed), str(wb_mode), str(yield_every), str(remote_touches), str(hands)],
                            capture_output=True, text=True, timeout=300, env=env)
         assert r.returncode == 0, (r.stdout, r.stderr[-2000:])
         out = json.loads(r.stdout.strip().splitlines()[-1])
