@@ -110,6 +110,63 @@ def measure_link(gv, torch, np):
     return res
 
 
+def measure_hit_path(gv, torch, np, inputs, oracle, hbm_copy_GBps):
+    """Hits only: a 64 MiB uint32 array with a pool that holds all of it, warm, read
+    through the paged view - uniform random indices on 4 KiB and on 64 KiB pages,
+    and unit stride - against the same gather on a plain array in HBM.  Per
+    element the gather moves 4 B of index, 4 B of data and 4 B of output; the
+    roofline object prices those 12 B against the HBM copy rate measured in this
+    process (random 4-byte reads cost a 64-byte sector each, which is why the
+    plain array is far from it too)."""
+    n_elems = 1 << 24
+    data = inputs.u32_values(0x9E3779B9, 0, n_elems)
+    arr = gv.pinned_array(data.shape, data.dtype)
+    arr[...] = data
+    d_plain = torch.from_numpy(data.view(np.int32)).cuda()
+    res = {}
+
+    def best_ms(fn, reps=7):
+        ts = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            e0, e1 = ev_pair(torch)
+            e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return min(ts)
+
+    for name, page, idx in (("random_4KiB_pages", 4096, inputs.u32_indices(1, 0, 1 << 22, n_elems)),
+                            ("random_64KiB_pages", 65536, inputs.u32_indices(1, 0, 1 << 22, n_elems)),
+                            ("unit_stride_4KiB_pages", 4096, np.arange(n_elems, dtype=np.uint32)),
+                            ("unit_stride_64KiB_pages", 65536, np.arange(n_elems, dtype=np.uint32))):
+        n = idx.size
+        d_idx = torch.from_numpy(idx.view(np.int32)).cuda()
+        d_out = torch.zeros(n, dtype=torch.int32, device="cuda")
+        want, _ = oracle.gather(data, idx)
+        vm = gv.gpuvm_create(arr.ctypes.data, arr.nbytes, page, arr.nbytes, gv.POLICY_CLOCK)
+        try:
+            for _ in range(2):
+                gv.gpuvm_run_gather(vm, d_idx, n, d_out, None)
+            gv.gpuvm_check(vm)
+            f0 = gv.gpuvm_stats(vm)["faults"]
+            ms = best_ms(lambda: gv.gpuvm_run_gather(vm, d_idx, n, d_out, None))
+            ok = bool(np.array_equal(d_out.cpu().numpy().view(np.uint32), want))
+            new_faults = gv.gpuvm_stats(vm)["faults"] - f0
+        finally:
+            gv.gpuvm_destroy(vm)
+        ms_plain = best_ms(lambda: gv.gpuvm_bench_gather_plain(d_plain, d_idx, n, d_out))
+        ok_plain = bool(np.array_equal(d_out.cpu().numpy().view(np.uint32), want))
+        gbps = 12 * n / ms / 1e6
+        res[name] = {"G_elem_per_s": round(n / ms / 1e6, 2), "plain_array_G_elem_per_s": round(n / ms_plain / 1e6, 2),
+                     "frac_of_plain_array": round(ms_plain / ms, 3), "best_ms": round(ms, 4), "elements": n,
+                     "new_faults": new_faults, "parity": ok and ok_plain,
+                     "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": hbm_copy_GBps, "unit": "GB/s",
+                                  "frac": round(gbps / hbm_copy_GBps, 4), "algorithmic_bytes_per_element": 12}}
+        del d_idx, d_out
+    gv.free_pinned(arr)
+    return res
+
+
 class GatherWorkload:
     """Random gather: 64 MiB uint32 host array, 4 KiB pages, 16 MiB pool, 2^20 indices."""
     name = "random_gather_64MiB_u32_4KiB_pages_16MiB_pool_2^20_idx"
@@ -1223,7 +1280,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": W.dtype, "data": "synthetic",
         "config": dict({"workload": W.name, "page_bytes": W.page, "frame_pool_bytes": W.pool,
-                        "policy": args.policy, "waves_in_flight": (gv.gpuvm_max_waves_duplex if args.workload == "scatter" else gv.gpuvm_max_waves)(W.vm),
+                        "policy": args.policy, "waves_in_flight": (gv.gpuvm_max_waves_duplex if args.workload == "scatter" else
+                                            gv.gpuvm_max_waves_streaming if args.workload in ("stream", "embedding") else gv.gpuvm_max_waves)(W.vm),
                         "oversubscription": round(W.arr.nbytes / W.pool, 2)}, **W.config()),
         "faults_per_s": round(st["faults"] / step_s, 1),
         "faults_per_step": st["faults"],
@@ -1304,6 +1362,8 @@ def main():
                 "sample": par_sample, "job_seconds": round(par_s, 6),
             }
     out["job_seconds"] = job
+    if args.workload == "gather":
+        out["hit_path"] = measure_hit_path(gv, torch, np, inputs, oracle, link["hbm_copy_rw"])
     if "gpu_zero_copy" in job:                       # the shortfall (or gain) against reading host memory in place
         out["paging_vs_zero_copy_same_gpu"] = round(job["gpu_zero_copy"] / job["gpu_paging"], 4)
     print(json.dumps(out), flush=True)

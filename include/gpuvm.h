@@ -209,7 +209,8 @@ GPUVM_API int gpuvm_set_remote_first(gpuvm_t *vm, size_t bytes_per_touch);
  * launch never uses more wavefronts than half the frames).  Left alone, the
  * scatter-increment launcher, whose faults write back as much as they fetch,
  * uses fewer: about 4 MiB of page traffic in flight, where the link's two
- * directions together peak.  A value set here (or GPUVM_WAVES_PER_CU in the
+ * directions together peak; so do the streaming, embedding and fault-ahead
+ * launchers on a pool smaller than the data set (gpuvm_max_waves_streaming).  A value set here (or GPUVM_WAVES_PER_CU in the
  * environment) is used as it is by every launcher. */
 GPUVM_API int gpuvm_set_waves_per_cu(gpuvm_t *vm, int waves_per_cu);
 
@@ -219,7 +220,8 @@ GPUVM_API int gpuvm_check(gpuvm_t *vm, void *stream);
 
 /* Largest number of wavefronts a launcher will keep in flight on this handle:
  * each wave holds at most one pinned page plus one frame under migration, so
- * it is min(n_frames / 2, what the device can hold).  Kernels written against
+ * it is min(n_frames / 2, what the device can hold) - or simply what the device
+ * can hold if the pool has a frame for every page, where nothing is ever evicted.  Kernels written against
  * gpuvm_device.h must stay within it too (size the grid from it and stride
  * over the work); beyond it the bounded waits may end a launch with
  * GPUVM_EDEADLK. */
@@ -227,6 +229,11 @@ GPUVM_API int gpuvm_max_waves(const gpuvm_t *vm);
 /* The same for the launchers whose faults write back as much as they fetch
  * (gpuvm_run_scatter_increment); see gpuvm_set_waves_per_cu. */
 GPUVM_API int gpuvm_max_waves_duplex(const gpuvm_t *vm);
+/* The same for the launchers that are plain streams of page faults with little
+ * work per page (gpuvm_run_stream_reduce, _embedding_bag, _prefetch): on a pool
+ * smaller than the data set they keep about 4 MiB of page traffic in flight,
+ * which fills the link; more only queues in front of the other memory traffic. */
+GPUVM_API int gpuvm_max_waves_streaming(const gpuvm_t *vm);
 
 /* Write every DIRTY page back to host_buf and clear the dirty bits; pages stay
  * resident (not in the paper, whose write-back happens only at eviction:

@@ -316,7 +316,9 @@ GPUVM_DEV void copy_frame_to_host(char *host, const char *frame, unsigned int by
 GPUVM_DEV bool touch_in_place(const gpuvm_dev_t &vm, unsigned int page) {
     const unsigned long long limit = vm.flags >> GPUVM_F_REMOTE_SHIFT;
     unsigned long long cur = a_load(vm.pte + page);
-    for (int tries = 0; tries < 4; ++tries) {
+    /* (a failed CAS returns the word as it is now; waves that walk an index array in
+     * step can meet on one word, so a few failures are not yet a reason to migrate) */
+    for (int tries = 0; tries < 32; ++tries) {
         if (((cur & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) != GPUVM_ST_INVALID) return false;
         if ((cur >> GPUVM_PTE_FRAME_SHIFT) + 1 >= limit) return false;
         if (a_cas(vm.pte + page, &cur, cur + (1ull << GPUVM_PTE_FRAME_SHIFT))) {
@@ -904,6 +906,140 @@ __device__ __forceinline__ void gpuvm_atomic_add_if(const gpuvm_dev_t &vm, unsig
 template <typename T>
 __device__ __forceinline__ void gpuvm_atomic_add(const gpuvm_dev_t &vm, unsigned long long elem, T v) {
     gpuvm_atomic_add_if<T>(vm, elem, v, true);
+}
+
+/* Several independent reads per lane in one optimistic transaction: the N page
+ * words, then the N elements, one wait, the N re-checks - N loads in flight per
+ * lane where gpuvm_load has one.  For code whose wave count is bounded by a
+ * small pool, so that more waves cannot hide the latency of the three dependent
+ * loads of a read.  Lanes whose read did not validate, or whose page is not
+ * resident, go through the miss pass one element index at a time.  Called by
+ * all lanes of the wave together; want[k] is the lane's predicate for elem[k]. */
+template <typename T, int N>
+__device__ __forceinline__ void gpuvm_load_n(const gpuvm_dev_t &vm, const unsigned long long (&elem)[N],
+                                             const bool (&want)[N], T (&out)[N]) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "gpuvm_load_n: 4- or 8-byte elements");
+    using namespace gpuvm_detail;
+    unsigned int page[N], off[N];
+    unsigned long long word[N], seen[N];
+    bool resident[N];
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const unsigned long long byte = elem[k] * sizeof(T);
+        page[k] = (unsigned int)(byte >> vm.page_shift);
+        off[k] = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
+        word[k] = want[k] ? a_load(vm.pte + page[k]) : 0ull;
+        out[k] = T{};
+    }
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        resident[k] = want[k] && ((word[k] & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT;
+        if (resident[k])
+            out[k] = __hip_atomic_load(reinterpret_cast<T *>(vm.frames + ((size_t)(word[k] >> GPUVM_PTE_FRAME_SHIFT) << vm.page_shift) + off[k]),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    wait_vm();
+#pragma unroll
+    for (int k = 0; k < N; ++k) seen[k] = resident[k] ? a_load(vm.pte + page[k]) : word[k];
+#pragma unroll
+    for (int k = 0; k < N; ++k)
+        if (resident[k]) resident[k] = optimistic_read_stands(vm, page[k], word[k], seen[k], true);
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        if (vm.flags & GPUVM_F_ACCESS_STATS) {
+            const unsigned int n_groups = count_page_groups(page[k], want[k]);
+            const unsigned int n_missing = count_page_groups(page[k], want[k] && !resident[k]);
+            const unsigned long long wanting = __builtin_amdgcn_ballot_w64(want[k]);
+            if (wave_now().leader) {
+                stat_add(vm, GPUVM_S_GROUPS, n_groups);
+                stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(wanting) - n_groups);
+                stat_add(vm, GPUVM_S_HITS, n_groups - n_missing);
+            }
+        }
+        T &slot = out[k];
+        access_missing<T>(vm, page[k], off[k], false, want[k] && !resident[k], seen[k],
+                          [&](T *p) { slot = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); },
+                          [&](T *p) { slot = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM); });
+    }
+}
+
+/* A wave's cursor over a paged array, for code that walks it with unit stride
+ * (or stays inside one page for many calls): the wave keeps ONE page pinned
+ * between calls - the paper's reference counter, held for as long as the wave
+ * stands on the page - so that a call that stays on the page is a compare and a
+ * load, with no look at the page table at all.  Moving to another page drops
+ * the pin and takes the next one (faulting the page in if need be); a call whose
+ * lanes stand on several pages drops the pin and goes through gpuvm_load /
+ * gpuvm_store lane by lane.  All lanes of the wave call together with the
+ * lane's predicate in `want`; the cursor itself is the same in every lane.
+ * The pin counts against the wave's one-frame-per-handle budget like a
+ * gpuvm_acquire, and like it must be given back: gpuvm_cursor_end() before the
+ * wave leaves, and no gpuvm_acquire on the same handle while a cursor is open. */
+struct gpuvm_cursor_t {
+    unsigned int page;        /* GPUVM_NO_PAGE: nothing pinned */
+    bool dirty;               /* the pinned page is already marked DIRTY */
+    char *frame;
+};
+__device__ __forceinline__ gpuvm_cursor_t gpuvm_cursor_begin() { return gpuvm_cursor_t{GPUVM_NO_PAGE, false, nullptr}; }
+__device__ __forceinline__ void gpuvm_cursor_end(const gpuvm_dev_t &vm, gpuvm_cursor_t &c) {
+    if (c.page != GPUVM_NO_PAGE) gpuvm_release(vm, c.page);
+    c.page = GPUVM_NO_PAGE;
+}
+namespace gpuvm_detail {
+/* true: the cursor now stands on the one page all wanting lanes are on (frame
+ * pinned, DIRTY set if write); false: the lanes are on several pages, or nobody
+ * wants anything - the cursor holds nothing and the caller takes the general path */
+GPUVM_DEV bool cursor_seek(const gpuvm_dev_t &vm, gpuvm_cursor_t &c, unsigned int page, bool want, bool write) {
+    const unsigned long long wanting = __builtin_amdgcn_ballot_w64(want);
+    if (wanting == 0) return false;
+    const bool count = (vm.flags & GPUVM_F_ACCESS_STATS) != 0;
+    if (__builtin_amdgcn_ballot_w64(want && page != c.page) == 0) {          /* still on the pinned page */
+        if (count && wave_now().leader) {
+            stat_add(vm, GPUVM_S_GROUPS, 1);
+            stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(wanting) - 1);
+            stat_add(vm, GPUVM_S_HITS, 1);
+        }
+        if (write && !c.dirty) {
+            if (wave_now().leader) a_or(vm.pte + c.page, GPUVM_PTE_DIRTY);  /* pinned: the word cannot leave RESIDENT */
+            c.dirty = true;
+        }
+        return true;
+    }
+    const unsigned int first = (unsigned int)__ffsll((long long)wanting) - 1u;
+    const unsigned int p = __builtin_amdgcn_readlane(page, first);
+    if (c.page != GPUVM_NO_PAGE) { gpuvm_release(vm, c.page); c.page = GPUVM_NO_PAGE; }
+    if (__builtin_amdgcn_ballot_w64(want && page != p) != 0) return false;   /* several pages */
+    if (count && wave_now().leader) {                                         /* (acquire_page counts the hit, or the fault) */
+        stat_add(vm, GPUVM_S_GROUPS, 1);
+        stat_add(vm, GPUVM_S_COALESCED, (unsigned long long)__popcll(wanting) - 1);
+    }
+    c.frame = acquire_page(vm, p, write, true);
+    c.page = p;
+    c.dirty = write;
+    return true;
+}
+}  // namespace gpuvm_detail
+template <typename T>
+__device__ __forceinline__ T gpuvm_cursor_load(const gpuvm_dev_t &vm, gpuvm_cursor_t &c, unsigned long long elem, bool want) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "gpuvm_cursor_load: 4- or 8-byte elements");
+    const unsigned long long byte = elem * sizeof(T);
+    const unsigned int page = (unsigned int)(byte >> vm.page_shift);
+    const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
+    if (gpuvm_detail::cursor_seek(vm, c, page, want, false))
+        return want ? __hip_atomic_load(reinterpret_cast<T *>(c.frame + off), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : T{};
+    return gpuvm_load_if<T>(vm, elem, want);
+}
+template <typename T>
+__device__ __forceinline__ void gpuvm_cursor_store(const gpuvm_dev_t &vm, gpuvm_cursor_t &c, unsigned long long elem, T v, bool want) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "gpuvm_cursor_store: 4- or 8-byte elements");
+    const unsigned long long byte = elem * sizeof(T);
+    const unsigned int page = (unsigned int)(byte >> vm.page_shift);
+    const unsigned int off = (unsigned int)(byte & ((1ull << vm.page_shift) - 1));
+    if (gpuvm_detail::cursor_seek(vm, c, page, want, true)) {
+        if (want) __hip_atomic_store(reinterpret_cast<T *>(c.frame + off), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    gpuvm_store_if<T>(vm, elem, v, want);
 }
 
 /* Array-like view for kernels written in the style of the paper's listing

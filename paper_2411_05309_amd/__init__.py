@@ -76,6 +76,7 @@ _SIGNATURES = {
     "gpuvm_check": ([C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_max_waves": ([C.c_void_p], C.c_int),
     "gpuvm_max_waves_duplex": ([C.c_void_p], C.c_int),
+    "gpuvm_max_waves_streaming": ([C.c_void_p], C.c_int),
     "gpuvm_flush": ([C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_reset": ([C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_stats": ([C.c_void_p, C.POINTER(Stats)], C.c_int),
@@ -220,6 +221,10 @@ def gpuvm_max_waves(vm):
 
 def gpuvm_max_waves_duplex(vm):
     return load().gpuvm_max_waves_duplex(vm)
+
+
+def gpuvm_max_waves_streaming(vm):
+    return load().gpuvm_max_waves_streaming(vm)
 
 
 def gpuvm_flush(vm, stream=None):

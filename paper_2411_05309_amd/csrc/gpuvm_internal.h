@@ -41,6 +41,7 @@ struct gpuvm {
     unsigned int phase_tag = 0;
     int *bfs_changed = nullptr;
     unsigned int *page_owner = nullptr;   // [n_pages + 1], edge-balanced BFS
+    unsigned char *page_marks = nullptr;  // [2][n_pages], edge-balanced BFS / SSSP: pages with active edges, this round and next
     unsigned int *row_progress = nullptr; // [8192] row reached by each compute wave (column-order product)
 };
 
@@ -58,6 +59,7 @@ struct gpuvm {
 int check_kernel_error(gpuvm_t *vm);      // reads the error word a kernel may have recorded (synchronous copy)
 int grid_for_waves(int waves);            // workgroups for that many wavefronts
 int launch_waves(const gpuvm_t *vm, size_t work_waves);          // waves to keep in flight; 0 = pool too small
+int launch_waves_streaming(const gpuvm_t *vm, size_t work_waves);   // for launches that are plain streams of page faults
 int launch_waves_duplex(const gpuvm_t *vm, size_t work_waves);   // the same for launches that write back as much as they fetch
 gpuvm_dev_t dev_for_writers(const gpuvm_t *vm, int waves);       // device view for a launch that dirties pages, with `waves` in flight
 

@@ -9,24 +9,79 @@
 
 using namespace gpuvm_detail;
 
-// Random gather: one access per lane per iteration, grid-stride.  (Several
-// independent accesses per lane in flight were tried: with all pages resident
-// they gain nothing over the occupancy that is there anyway, and under
-// oversubscription a wave that collects four times as many misses per
-// iteration finds fewer of them resident by the time it reaches them - 10 %
-// more faults.)
+// Random gather.  A wave takes a contiguous run of the index array, 64 indices
+// per step, and reads through a cursor: when all of a step's indices fall on the
+// page the wave already stands on (a sorted or unit-stride index array) the read
+// needs no look at the page table; otherwise - the random case - every lane
+// goes through gpuvm_load on its own.
+// PER_LANE = 1: one access per lane per step - the form for a pool smaller than
+// the data set: a wave that collects four times as many misses per step finds
+// fewer of them resident by the time it reaches them (10 % more faults on the
+// 4x oversubscribed gather).  PER_LANE = 4 is for a pool that holds every page,
+// where nothing is ever evicted and the run is hits after the first touch: four
+// reads in flight per lane (four cursor reads when every 64-lane group of the
+// step stays on one page, one batched optimistic read otherwise).
+template <int PER_LANE>
 __global__ __launch_bounds__(kBlock) void k_gather(gpuvm_dev_t vm, const uint32_t *__restrict__ idx, size_t n,
                                                     uint32_t *__restrict__ out, unsigned long long *sum,
                                                     unsigned long long n_elems) {
-    const size_t nthreads = (size_t)gridDim.x * kBlock;
+    const unsigned int lane = threadIdx.x & 63;
+    const size_t wave = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
+    const size_t step = 64 * PER_LANE;
+    const size_t per_wave = ((n + nwaves - 1) / nwaves + step - 1) / step * step;   // whole steps
+    const size_t lo = wave * per_wave, hi = lo + per_wave < n ? lo + per_wave : n;
     unsigned long long acc = 0;
-    const size_t n_up = (n + 63) & ~(size_t)63;                  // whole waves iterate together
-    for (size_t k = (size_t)blockIdx.x * kBlock + threadIdx.x; k < n_up; k += nthreads) {
-        unsigned long long i = k < n ? idx[k] : 0;
-        bool want = k < n;
-        if (want && i >= n_elems) { raise_error(vm, GPUVM_ERANGE); want = false; }
-        const uint32_t v = gpuvm_load_if<uint32_t>(vm, i, want);
-        if (want) { out[k] = v; acc += v; }
+    if constexpr (PER_LANE == 1) {
+        gpuvm_cursor_t cur = gpuvm_cursor_begin();
+        for (size_t k0 = lo; k0 < hi; k0 += 64) {
+            const size_t k = k0 + lane;
+            unsigned long long i = k < hi ? idx[k] : 0;
+            bool want = k < hi;
+            if (want && i >= n_elems) { raise_error(vm, GPUVM_ERANGE); want = false; }
+            const uint32_t v = gpuvm_cursor_load<uint32_t>(vm, cur, i, want);
+            if (want) { out[k] = v; acc += v; }
+        }
+        gpuvm_cursor_end(vm, cur);
+    } else {
+        gpuvm_cursor_t cur = gpuvm_cursor_begin();
+        uint32_t ahead[PER_LANE];                                // the next step's indices, loaded a step early
+#pragma unroll
+        for (int j = 0; j < PER_LANE; ++j) ahead[j] = lo + j * 64 + lane < hi ? idx[lo + j * 64 + lane] : 0u;
+        for (size_t k0 = lo; k0 < hi; k0 += step) {
+            unsigned long long i[PER_LANE];
+            bool want[PER_LANE], stay = cur.page != GPUVM_NO_PAGE;
+#pragma unroll
+            for (int j = 0; j < PER_LANE; ++j) {
+                const size_t k = k0 + j * 64 + lane;
+                want[j] = k < hi;
+                i[j] = ahead[j];
+                ahead[j] = k + step < hi ? idx[k + step] : 0u;
+                if (want[j] && i[j] >= n_elems) { raise_error(vm, GPUVM_ERANGE); want[j] = false; }
+                stay = stay && !(want[j] && (unsigned int)((i[j] * 4) >> vm.page_shift) != cur.page);
+            }
+            if (__builtin_amdgcn_ballot_w64(!stay) == 0) {
+                // the whole step stays on the page the wave stands on: PER_LANE loads in flight, nothing else
+                uint32_t v[PER_LANE];
+#pragma unroll
+                for (int j = 0; j < PER_LANE; ++j)
+                    v[j] = want[j] ? __hip_atomic_load(reinterpret_cast<const uint32_t *>(cur.frame + ((i[j] * 4) & ((1ull << vm.page_shift) - 1))),
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+#pragma unroll
+                for (int j = 0; j < PER_LANE; ++j)
+                    if (want[j]) { out[k0 + j * 64 + lane] = v[j]; acc += v[j]; }
+            } else {
+                // one group of 64 after the other through the cursor (one copy of the general path)
+#pragma nounroll
+                for (int j = 0; j < PER_LANE; ++j) {
+                    const unsigned long long ij = j == 0 ? i[0] : j == 1 ? i[1] : j == 2 ? i[2] : i[PER_LANE - 1];
+                    const bool wj = j == 0 ? want[0] : j == 1 ? want[1] : j == 2 ? want[2] : want[PER_LANE - 1];
+                    const uint32_t v = gpuvm_cursor_load<uint32_t>(vm, cur, ij, wj);
+                    if (wj) { out[k0 + j * 64 + lane] = v; acc += v; }
+                }
+            }
+        }
+        gpuvm_cursor_end(vm, cur);
     }
     if (sum) {
         // every lane of the wave reaches this point (the loop has ended for all)
@@ -424,11 +479,23 @@ int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n, uint32_t *d_o
                      void *stream) {
     if (!vm || (n && (!d_idx || !d_out))) return GPUVM_EINVAL;
     if (n == 0) return GPUVM_OK;
-    const int waves = launch_waves(vm, (n + 63) / 64);
+    // every page fits, so nothing is ever evicted and the run is hits after the first
+    // touch: four reads in flight per lane, and as many waves as the device holds
+    // (hits are bound by latency, not by the link) unless the caller chose a count
+    const bool all_fit = vm->dev.n_frames >= vm->dev.n_pages;
+    int waves = launch_waves(vm, (n + 63) / 64);
+    if (all_fit && !vm->waves_chosen) {
+        long long cap = (long long)vm->cus * 32;                  // (no bound by the frames: nothing is ever evicted)
+        const long long need = (long long)((n + 255) / 256 + kWavesPerBlock - 1) / kWavesPerBlock * kWavesPerBlock;
+        waves = (int)std::max<long long>(std::min(cap, need), std::min<long long>(waves, kWavesPerBlock));
+    }
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
-    k_gather<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, d_out,
-                                                                         (unsigned long long *)d_sum,
-                                                                         vm->dev.bytes / 4);
+    if (all_fit && n >= (size_t)waves * 256)
+        k_gather<4><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, d_out,
+                                                                                (unsigned long long *)d_sum, vm->dev.bytes / 4);
+    else
+        k_gather<1><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, d_out,
+                                                                                (unsigned long long *)d_sum, vm->dev.bytes / 4);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }
@@ -497,7 +564,7 @@ int gpuvm_run_prefetch(gpuvm_t *vm, size_t first_page, size_t n_pages, void *str
     if (!vm) return GPUVM_EINVAL;
     if (first_page > vm->dev.n_pages || n_pages > vm->dev.n_pages - first_page) return GPUVM_ERANGE;
     if (n_pages == 0) return GPUVM_OK;
-    const int waves = launch_waves(vm, n_pages);
+    const int waves = launch_waves_streaming(vm, n_pages);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
     k_prefetch<<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, (unsigned int)first_page,
                                                                            (unsigned int)n_pages);
@@ -511,7 +578,7 @@ int gpuvm_run_stream_reduce(gpuvm_t *vm, size_t block_elems, double *d_sums, voi
     if (block_bytes % vm->page_bytes || vm->dev.bytes % 4) return GPUVM_EINVAL;
     const unsigned int ppb = (unsigned int)(block_bytes / vm->page_bytes);
     const size_t nblocks = (vm->dev.n_pages + ppb - 1) / ppb;
-    const int waves = launch_waves(vm, vm->dev.n_pages);
+    const int waves = launch_waves_streaming(vm, vm->dev.n_pages);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
     hipStream_t s = (hipStream_t)stream;
     k_fill64<<<64, 256, 0, s>>>((unsigned long long *)d_sums, nblocks, 0ull);   // +0.0
@@ -528,7 +595,7 @@ static int run_embedding_bag(gpuvm_t *vm, size_t dim, const int32_t *d_ids, size
     if (vm->page_bytes % row_bytes || vm->dev.bytes % row_bytes) return GPUVM_EINVAL;
     if (bags == 0) return GPUVM_OK;
     // the zero-copy baseline holds no frames: its waves are bounded by the device only
-    const int waves = direct ? vm->cus * vm->waves_per_cu : launch_waves(vm, bags);
+    const int waves = direct ? vm->cus * vm->waves_per_cu : launch_waves_streaming(vm, bags);
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
     const int grid = grid_for_waves(waves);
     hipStream_t s = (hipStream_t)stream;

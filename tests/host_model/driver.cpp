@@ -82,6 +82,15 @@ int main(int argc, char **argv) {
             if (op == 7) {                                        // store to / read back a private element
                 const unsigned k = (x >> 40) % priv;
                 const u64 e = k * stride + t;
+                if (x & 0x100) {                                  // through a cursor: the page stays pinned between the two
+                    gpuvm_cursor_t c = gpuvm_cursor_begin();
+                    const u64 got = gpuvm_cursor_load<u64>(vm, c, e, true);
+                    if (got != last[t][k]) fail("private element read back (cursor)", e, got, last[t][k]);
+                    last[t][k] = x | 1;
+                    gpuvm_cursor_store<u64>(vm, c, e, last[t][k], true);
+                    gpuvm_cursor_end(vm, c);
+                    continue;
+                }
                 const u64 got = gpuvm_load<u64>(vm, e);
                 if (got != last[t][k]) fail("private element read back", e, got, last[t][k]);
                 last[t][k] = x | 1;
@@ -101,6 +110,27 @@ int main(int argc, char **argv) {
                                        __HIP_MEMORY_SCOPE_AGENT);
                 gpuvm_release(vm, page);
                 completed[i].fetch_add(1);
+            } else if (op == 3 && (x & 0x100)) {                  // two reads in one optimistic transaction
+                const u64 j = (x >> 20) % n_shared;
+                if (owner_of(j) >= 0) continue;
+                const u64 lo_i = completed[i].load(), lo_j = completed[j].load();
+                const unsigned long long elems[2] = {i, j};
+                const bool wants[2] = {true, true};
+                u64 got[2];
+                gpuvm_load_n<u64, 2>(vm, elems, wants, got);
+                const u64 hi_i = announced[i].load(), hi_j = announced[j].load();
+                if (got[0] < init_val[i] + lo_i || got[0] > init_val[i] + hi_i) fail("batched read out of bounds", i, got[0], init_val[i]);
+                if (got[1] < init_val[j] + lo_j || got[1] > init_val[j] + hi_j) fail("batched read out of bounds", j, got[1], init_val[j]);
+            } else if (op == 4 && (x & 0x100)) {                  // a short walk with a cursor (may cross into the next page)
+                gpuvm_cursor_t c = gpuvm_cursor_begin();
+                for (u64 e = i; e < i + 6 && e < n_shared; ++e) {
+                    if (owner_of(e) >= 0) continue;
+                    const u64 lo = completed[e].load();
+                    const u64 got = gpuvm_cursor_load<u64>(vm, c, e, true);
+                    const u64 hi = announced[e].load();
+                    if (got < init_val[e] + lo || got > init_val[e] + hi) fail("cursor read out of bounds", e, got, init_val[e]);
+                }
+                gpuvm_cursor_end(vm, c);
             } else if (op <= 4) {                                 // read through the element accessor
                 const u64 lo = completed[i].load();
                 const u64 got = gpuvm_load<u64>(vm, i);
