@@ -143,6 +143,22 @@ GPUVM_API int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes,
                            size_t frame_pool_bytes, int policy, gpuvm_t **out);
 GPUVM_API int gpuvm_destroy(gpuvm_t *vm);
 
+/* The same view with its frame pool, page table, frame table, cursor and
+ * counters carved out of device memory the caller owns (say, one torch tensor)
+ * instead of allocated by the library (paper: Multi-kernel support - the GPU
+ * pool is set up once, statically).  gpuvm_workspace_bytes() says how large
+ * that memory must be for a given geometry (0 if the geometry is one that
+ * gpuvm_create would refuse); d_workspace must be a device pointer on a
+ * 256-byte boundary with at least that many bytes (GPUVM_EINVAL otherwise),
+ * stays the caller's, must outlive the handle and must not be touched while
+ * the handle lives.  gpuvm_destroy() leaves it alone.  Everything else is as
+ * for gpuvm_create; the few launchers that keep scratch of their own (the
+ * deterministic mode, the edge-balanced graph launchers, the column-order
+ * product) still allocate it on first use. */
+GPUVM_API size_t gpuvm_workspace_bytes(size_t bytes, size_t page_bytes, size_t frame_pool_bytes);
+GPUVM_API int gpuvm_create_in(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_pool_bytes,
+                              int policy, void *d_workspace, size_t workspace_bytes, gpuvm_t **out);
+
 /* Copy of the device-side view, for callers that write their own kernels with
  * gpuvm_device.h. */
 GPUVM_API int gpuvm_device_handle(const gpuvm_t *vm, gpuvm_dev_t *out);

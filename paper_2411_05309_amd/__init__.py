@@ -67,6 +67,8 @@ _SIGNATURES = {
     "gpuvm_host_free": ([C.c_void_p], C.c_int),
     "gpuvm_create": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_size_t, C.c_int, C.POINTER(C.c_void_p)], C.c_int),
     "gpuvm_destroy": ([C.c_void_p], C.c_int),
+    "gpuvm_workspace_bytes": ([C.c_size_t, C.c_size_t, C.c_size_t], C.c_size_t),
+    "gpuvm_create_in": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)], C.c_int),
     "gpuvm_device_handle": ([C.c_void_p, C.POINTER(Dev)], C.c_int),
     "gpuvm_configure": ([C.c_void_p, C.c_uint32, C.c_int], C.c_int),
     "gpuvm_set_writeback_mode": ([C.c_void_p, C.c_int], C.c_int),
@@ -170,6 +172,17 @@ def gpuvm_host_free(ptr):
 def gpuvm_create(host_buf, nbytes, page_bytes, frame_pool_bytes, policy=POLICY_CLOCK):
     out = C.c_void_p()
     _call("gpuvm_create", _ptr(host_buf), nbytes, page_bytes, frame_pool_bytes, policy, C.byref(out))
+    return out.value
+
+
+def gpuvm_workspace_bytes(nbytes, page_bytes, frame_pool_bytes):
+    return int(load().gpuvm_workspace_bytes(nbytes, page_bytes, frame_pool_bytes))
+
+
+def gpuvm_create_in(host_buf, nbytes, page_bytes, frame_pool_bytes, policy, d_workspace, workspace_bytes):
+    out = C.c_void_p()
+    _call("gpuvm_create_in", _ptr(host_buf), nbytes, page_bytes, frame_pool_bytes, policy, _ptr(d_workspace), workspace_bytes,
+          C.byref(out))
     return out.value
 
 

@@ -128,16 +128,68 @@ int gpuvm_host_free(void *p) {
     return GPUVM_OK;
 }
 
+// Layout of pool and tables inside one device allocation (every part on a 256-byte boundary).
+namespace {
+struct table_layout { size_t frames, pte, owner, hand, stats, flag, total; };
+bool geometry_ok(size_t bytes, size_t page_bytes, size_t frame_pool_bytes) {
+    if (bytes == 0) return false;
+    if (page_bytes < 4096 || page_bytes > (1u << 20) || (page_bytes & (page_bytes - 1))) return false;
+    const size_t n_frames = frame_pool_bytes / page_bytes;
+    const size_t n_pages = (bytes + page_bytes - 1) / page_bytes;
+    return n_frames >= 2 && n_frames < (1u << 27) && n_pages < 0xFFFFFFFFull;
+}
+table_layout layout_for(size_t bytes, size_t page_bytes, size_t frame_pool_bytes) {
+    const size_t n_frames = frame_pool_bytes / page_bytes, n_pages = (bytes + page_bytes - 1) / page_bytes;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    table_layout l;
+    l.frames = 0;
+    l.pte = up(n_frames * page_bytes);
+    l.owner = l.pte + up(n_pages * sizeof(unsigned long long));
+    l.hand = l.owner + up(n_frames * sizeof(unsigned int));
+    l.stats = l.hand + up(2 * sizeof(unsigned long long));
+    l.flag = l.stats + up((size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT * sizeof(unsigned long long));
+    l.total = l.flag + up(sizeof(int));
+    return l;
+}
+}  // namespace
+
+static int create_view(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_pool_bytes, int policy,
+                       void *d_workspace, size_t workspace_bytes, gpuvm_t **out);
+
+size_t gpuvm_workspace_bytes(size_t bytes, size_t page_bytes, size_t frame_pool_bytes) {
+    return geometry_ok(bytes, page_bytes, frame_pool_bytes) ? layout_for(bytes, page_bytes, frame_pool_bytes).total : 0;
+}
+
 int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_pool_bytes, int policy,
                  gpuvm_t **out) {
+    return create_view(host_buf, bytes, page_bytes, frame_pool_bytes, policy, nullptr, 0, out);
+}
+
+int gpuvm_create_in(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_pool_bytes, int policy,
+                    void *d_workspace, size_t workspace_bytes, gpuvm_t **out) {
+    if (out) *out = nullptr;
+    if (!d_workspace || ((uintptr_t)d_workspace & 255)) return GPUVM_EINVAL;
+    return create_view(host_buf, bytes, page_bytes, frame_pool_bytes, policy, d_workspace, workspace_bytes, out);
+}
+
+static int create_view(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_pool_bytes, int policy,
+                       void *d_workspace, size_t workspace_bytes, gpuvm_t **out) {
     if (!out) return GPUVM_EINVAL;
     *out = nullptr;
-    if (!host_buf || bytes == 0) return GPUVM_EINVAL;
-    if (page_bytes < 4096 || page_bytes > (1u << 20) || (page_bytes & (page_bytes - 1))) return GPUVM_EINVAL;
+    if (!host_buf || !geometry_ok(bytes, page_bytes, frame_pool_bytes)) return GPUVM_EINVAL;
     if (policy < GPUVM_POLICY_FIFO || policy > GPUVM_POLICY_GCLOCK) return GPUVM_EINVAL;
     const size_t n_frames = frame_pool_bytes / page_bytes;
     const size_t n_pages = (bytes + page_bytes - 1) / page_bytes;
-    if (n_frames < 2 || n_frames >= (1u << 27) || n_pages >= 0xFFFFFFFFull) return GPUVM_EINVAL;
+    const table_layout lay = layout_for(bytes, page_bytes, frame_pool_bytes);
+    if (d_workspace) {
+        if (workspace_bytes < lay.total) return GPUVM_EINVAL;
+        hipPointerAttribute_t wa;                                 // the workspace must be device memory, all of it
+        if (hipPointerGetAttributes(&wa, d_workspace) != hipSuccess || wa.type != hipMemoryTypeDevice ||
+            hipPointerGetAttributes(&wa, (char *)d_workspace + lay.total - 1) != hipSuccess || wa.type != hipMemoryTypeDevice) {
+            (void)hipGetLastError();
+            return GPUVM_EINVAL;
+        }
+    }
 
     hipPointerAttribute_t attr;
     if (hipPointerGetAttributes(&attr, host_buf) != hipSuccess) { (void)hipGetLastError(); return GPUVM_EPIN; }
@@ -177,16 +229,27 @@ int gpuvm_create(void *host_buf, size_t bytes, size_t page_bytes, size_t frame_p
     if (policy == GPUVM_POLICY_CLOCK || policy == GPUVM_POLICY_CLOCK_WRITE_AWARE)
         d.flags |= (uint32_t)GPUVM_CLOCK_HANDS_DEFAULT << GPUVM_F_HANDS_SHIFT;
     int rc = GPUVM_OK;
-    auto alloc = [&](void **p, size_t sz) {
-        if (rc) return;
-        if (hipMalloc(p, sz) != hipSuccess) { (void)hipGetLastError(); rc = GPUVM_ENOMEM; }
-    };
-    alloc((void **)&d.frames, n_frames * page_bytes);
-    alloc((void **)&d.pte, n_pages * sizeof(unsigned long long));
-    alloc((void **)&d.frame_owner, n_frames * sizeof(unsigned int));
-    alloc((void **)&d.hand, 2 * sizeof(unsigned long long));
-    alloc((void **)&d.stats, (size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT * sizeof(unsigned long long));
-    alloc((void **)&vm->bfs_changed, sizeof(int));
+    if (d_workspace) {
+        char *w = (char *)d_workspace;
+        vm->owns_tables = false;
+        d.frames = w + lay.frames;
+        d.pte = (unsigned long long *)(w + lay.pte);
+        d.frame_owner = (unsigned int *)(w + lay.owner);
+        d.hand = (unsigned long long *)(w + lay.hand);
+        d.stats = (unsigned long long *)(w + lay.stats);
+        vm->bfs_changed = (int *)(w + lay.flag);
+    } else {
+        auto alloc = [&](void **p, size_t sz) {
+            if (rc) return;
+            if (hipMalloc(p, sz) != hipSuccess) { (void)hipGetLastError(); rc = GPUVM_ENOMEM; }
+        };
+        alloc((void **)&d.frames, n_frames * page_bytes);
+        alloc((void **)&d.pte, n_pages * sizeof(unsigned long long));
+        alloc((void **)&d.frame_owner, n_frames * sizeof(unsigned int));
+        alloc((void **)&d.hand, 2 * sizeof(unsigned long long));
+        alloc((void **)&d.stats, (size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT * sizeof(unsigned long long));
+        alloc((void **)&vm->bfs_changed, sizeof(int));
+    }
     if (rc) { gpuvm_destroy(vm); return rc; }
     k_fill64<<<256, 256>>>(d.pte, n_pages, 0ull);
     k_fill32<<<256, 256>>>(d.frame_owner, n_frames, GPUVM_NO_PAGE);
@@ -201,9 +264,12 @@ int gpuvm_destroy(gpuvm_t *vm) {
     if (!vm) return GPUVM_OK;
     (void)hipDeviceSynchronize();
     gpuvm_dev_t &d = vm->dev;
-    (void)hipFree(d.frames); (void)hipFree(d.pte); (void)hipFree(d.frame_owner); (void)hipFree(d.hand); (void)hipFree(d.stats);
+    if (vm->owns_tables) {
+        (void)hipFree(d.frames); (void)hipFree(d.pte); (void)hipFree(d.frame_owner); (void)hipFree(d.hand); (void)hipFree(d.stats);
+        (void)hipFree(vm->bfs_changed);
+    }
     (void)hipFree(vm->stamp); (void)hipFree(vm->first); (void)hipFree(vm->miss); (void)hipFree(vm->miss_sorted); (void)hipFree(vm->jobs);
-    (void)hipFree(vm->phase_ctr); (void)hipFree(vm->bfs_changed); (void)hipFree(vm->page_owner); (void)hipFree(vm->page_marks); (void)hipFree(vm->row_progress);
+    (void)hipFree(vm->phase_ctr); (void)hipFree(vm->page_owner); (void)hipFree(vm->page_marks); (void)hipFree(vm->row_progress);
     delete vm;
     return GPUVM_OK;
 }

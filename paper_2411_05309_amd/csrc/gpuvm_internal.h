@@ -29,6 +29,7 @@ struct gpuvm {
     int waves_per_cu;
     bool waves_chosen;            // set by the caller (or the environment): launchers do not second-guess it
     bool wb_chosen = false;       // write-back order set by the caller: launchers do not second-guess it
+    bool owns_tables = true;      // false: pool and tables were carved from the caller's workspace (gpuvm_create_in)
     size_t page_bytes;
     // deterministic mode scratch (allocated on first use)
     unsigned int *stamp = nullptr;        // [n_pages] phase tag of the last toucher
