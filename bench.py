@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--clock-hands", type=int, default=None, metavar="EIGHTHS",
                     help="CLOCK policies: front hand this many eighths of the ring ahead of the cursor (0 = one hand; default 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-baselines", action="store_true",
+                    help="skip the same-GPU baselines, the hit-path measurements and the dedup step (profiling runs)")
     ap.add_argument("--bfs-naive", action="store_true", help="BFS with vertex-chunk instead of edge-balanced work")
     ap.add_argument("--remote-first", type=int, default=0, metavar="BYTES",
                     help="serve read misses in place until a page has cost its migration; BYTES = what a wavefront reads "
@@ -1313,13 +1315,13 @@ def main():
             if len(parts) > 2 and parts[0] == args.workload and parts[1] == W.kernel:
                 kv = {k: float(v) for k, v in (p.split("=") for p in parts[2:])}
                 scale = st["faults"] / kv["faults"]
-                out["roofline"]["traffic"] = int((kv["host_link_read"] + kv["hbm_read"] + kv["hbm_write"]) * scale)
+                out["roofline"]["traffic"] = int((kv["host_link_read"] + kv.get("host_link_write", 0.0) + kv["hbm_read"] + kv["hbm_write"]) * scale)
                 out["roofline"]["traffic_detail"] = {k: int(v * scale) for k, v in kv.items() if k != "faults"}
                 out["roofline"]["traffic_source"] = "profiles/traffic_per_launch.txt (rocprofv3 --pmc), scaled by this run's fault count"
     # one more cold step, untimed, with the per-access counters on: what the
     # wavefront dedup and the inter-wave arbitration did (they are off in the
     # timed steps, where they would cost two ballots loops per access)
-    if args.workload in ("gather", "filter", "matvec_t", "matvec"):
+    if args.workload in ("gather", "filter", "matvec_t", "matvec") and not args.no_baselines:
         gv.gpuvm_configure(W.vm, 0, True)
         step()
         gv.gpuvm_check(W.vm)
@@ -1335,7 +1337,7 @@ def main():
             "note": "one untimed cold step with access statistics on",
         }
     job = {"gpu_paging": round(step_s, 6)}
-    if hasattr(W, "baselines"):
+    if hasattr(W, "baselines") and not args.no_baselines:
         out["baselines_same_gpu"] = W.baselines(oracle)
         for k, v in out["baselines_same_gpu"].items():
             if isinstance(v, dict) and k.startswith("zero_copy"):
@@ -1362,7 +1364,7 @@ def main():
                 "sample": par_sample, "job_seconds": round(par_s, 6),
             }
     out["job_seconds"] = job
-    if args.workload == "gather":
+    if args.workload == "gather" and not args.no_baselines:
         out["hit_path"] = measure_hit_path(gv, torch, np, inputs, oracle, link["hbm_copy_rw"])
     if "gpu_zero_copy" in job:                       # the shortfall (or gain) against reading host memory in place
         out["paging_vs_zero_copy_same_gpu"] = round(job["gpu_zero_copy"] / job["gpu_paging"], 4)

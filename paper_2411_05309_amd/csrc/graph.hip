@@ -90,15 +90,25 @@ __global__ void k_bfs_page_owner(const int64_t *__restrict__ row_ptr, int64_t nv
 // scattered reads) than the page itself is read in place; everything else is
 // paged in as usual.  The sparse levels of a BFS,
 // where a 64 KiB page is wanted for a handful of edges, are the case.
-// page_marks (may be null = every page): one byte per page of col_idx, non-zero if
-// some vertex that is active this round owns edges in the page; unmarked pages are
-// not looked at at all, so a round costs what its frontier's pages cost and not a
-// scan over the owner ranges of every vertex.
+// The pages of col_idx in which some active vertex owns edges: a mark per page and
+// the marked pages as a list (in no particular order), so that a round costs what
+// its frontier's pages cost - not a scan over the owner ranges of every vertex -
+// and the waves share the pages of a sparse round evenly.
+struct page_list_t {
+    unsigned int *mark;                            // [n_pages] 0 / 1
+    unsigned int *list;                            // [n_pages] the marked pages
+    unsigned int *count;                           // [1] how many
+};
+__device__ __forceinline__ void mark_page(const page_list_t &next, unsigned int p) {
+    if (next.mark[p] == 0 && atomicExch(next.mark + p, 1u) == 0) next.list[atomicAdd(next.count, 1u)] = p;
+}
+
+// `work` (may be null = every page): this round's page list.
 template <bool DIRECT = false, class Active, class Visit>
 __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gpuvm_dev_t *vm2,
                                                  const int64_t *__restrict__ row_ptr,
                                                  const unsigned int *__restrict__ page_owner,
-                                                 const unsigned char *__restrict__ page_marks,
+                                                 const page_list_t *work,
                                                  Active active, Visit visit) {
     const unsigned int lane = threadIdx.x & 63;
     const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
@@ -110,8 +120,9 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
     // scale-26 BFS a factor of 2 was the fastest of 1, 1.5, 2, 3, 4, 8
     // (206, 146, 139, 142, 146, 157 ms; 197 ms with every page migrated)
     constexpr unsigned long long kInPlacePenalty = 2;
-    for (unsigned int page = wave; page < vm.n_pages; page += nwaves) {
-        if (page_marks && !page_marks[page]) continue;
+    const unsigned int n_work = work ? *work->count : vm.n_pages;
+    for (unsigned int k = wave; k < n_work; k += nwaves) {
+        const unsigned int page = work ? work->list[k] : k;
         const int64_t e_lo = (int64_t)page << elems_shift;
         const int64_t e_hi = min((long long)n_edges, (long long)(e_lo + ((int64_t)1 << elems_shift)));
         const int64_t v_first = page_owner[page], v_last = page_owner[page + 1];
@@ -185,33 +196,32 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
 // A vertex has just become active for the next round: mark the pages of col_idx
 // that hold its edges.
 __device__ __forceinline__ void mark_pages_of(const int64_t *__restrict__ row_ptr, int64_t u, unsigned int elems_shift,
-                                              unsigned char *marks_next) {
+                                              const page_list_t &next) {
     const int64_t b = row_ptr[u], e = row_ptr[u + 1];
     if (e <= b) return;
-    for (int64_t p = b >> elems_shift; p <= (e - 1) >> elems_shift; ++p) marks_next[p] = 1;
+    for (int64_t p = b >> elems_shift; p <= (e - 1) >> elems_shift; ++p) mark_page(next, (unsigned int)p);
 }
 
 __global__ void k_mark_pages_of(const int64_t *__restrict__ row_ptr, int64_t u, unsigned int elems_shift,
-                                unsigned char *marks) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) mark_pages_of(row_ptr, u, elems_shift, marks);
+                                page_list_t next) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) mark_pages_of(row_ptr, u, elems_shift, next);
 }
 
 template <bool DIRECT>
 __global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
                                                                 const unsigned int *__restrict__ page_owner, int64_t nv,
-                                                                const unsigned char *__restrict__ marks_cur,
-                                                                unsigned char *marks_next,
+                                                                page_list_t work, page_list_t next,
                                                                 int32_t *level, int32_t cur, int *changed) {
     int found = 0;
     const unsigned int elems_shift = vm.page_shift - 2;
-    walk_owned_pages<DIRECT>(vm, nullptr, row_ptr, page_owner, marks_cur,
+    walk_owned_pages<DIRECT>(vm, nullptr, row_ptr, page_owner, &work,
                      [&](int64_t v) { return level[v] == cur; },
                      [&](int64_t, int32_t u, unsigned int, const char *, bool) {
                          if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); return; }   // malformed neighbour id
                          if (level[u] < 0) {
                              level[u] = cur + 1;
                              found = 1;
-                             mark_pages_of(row_ptr, u, elems_shift, marks_next);   // several lanes may find u: same marks
+                             mark_pages_of(row_ptr, u, elems_shift, next);         // several lanes may find u: same marks
                          }
                      });
     if (__builtin_amdgcn_ballot_w64(found != 0) && (threadIdx.x & 63) == 0) *changed = 1;
@@ -247,13 +257,12 @@ __global__ __launch_bounds__(kBlock) void k_cc_round_balanced(gpuvm_dev_t vm, co
 __global__ __launch_bounds__(kBlock) void k_sssp_round_balanced(gpuvm_dev_t vm, gpuvm_dev_t vmw,
                                                                  const int64_t *__restrict__ row_ptr,
                                                                  const unsigned int *__restrict__ page_owner, int64_t nv,
-                                                                 const unsigned char *__restrict__ marks_cur,
-                                                                 unsigned char *marks_next,
+                                                                 page_list_t work, page_list_t next,
                                                                  uint32_t *dist, const unsigned char *act_cur,
                                                                  unsigned char *act_next, int *changed) {
     int found = 0;
     const unsigned int elems_shift = vm.page_shift - 2;
-    walk_owned_pages(vm, &vmw, row_ptr, page_owner, marks_cur,
+    walk_owned_pages(vm, &vmw, row_ptr, page_owner, &work,
                      [&](int64_t v) { return act_cur[v] != 0; },
                      [&](int64_t v, int32_t u, unsigned int off, const char *pw, bool in_place) {
                          if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); return; }
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(kBlock) void k_sssp_round_balanced(gpuvm_dev_t vm, 
                              const uint32_t nd = dv + w;
                              const uint32_t old = __hip_atomic_fetch_min(dist + u, nd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                              if (nd < old) {
-                                 if (!act_next[u]) mark_pages_of(row_ptr, u, elems_shift, marks_next);   // first to lower it this round (or racing with the first)
+                                 if (!act_next[u]) mark_pages_of(row_ptr, u, elems_shift, next);   // first to lower it this round (or racing with the first)
                                  act_next[u] = 1;
                                  found = 1;
                              }
@@ -275,6 +284,18 @@ __global__ __launch_bounds__(kBlock) void k_sssp_round_balanced(gpuvm_dev_t vm, 
 
 __global__ void k_iota32(int32_t *p, size_t n) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = (int32_t)i;
+}
+
+// the two page lists of a handle (allocated by ensure_page_owner)
+static page_list_t page_list_of(const gpuvm_t *vm, int which) {
+    const size_t np = vm->dev.n_pages;
+    unsigned int *base = vm->page_marks + (size_t)which * (2 * np + 64);
+    return page_list_t{base, base + np, base + 2 * np};
+}
+static void clear_page_list(const gpuvm_t *vm, int which, hipStream_t s) {
+    const page_list_t l = page_list_of(vm, which);
+    k_fill32<<<64, 256, 0, s>>>(l.mark, vm->dev.n_pages, 0u);
+    k_fill32<<<1, 64, 0, s>>>(l.count, 1, 0u);
 }
 
 extern "C" {
@@ -296,24 +317,23 @@ static int run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t sr
     }
     k_fill32<<<1024, 256, 0, s>>>((unsigned int *)d_level, (size_t)nv, 0xFFFFFFFFu);
     k_fill32<<<1, 64, 0, s>>>((unsigned int *)d_level + src, 1, 0u);
-    const size_t np = vm->dev.n_pages;
     if (balanced) {                                            // the source's pages are the first round's work
-        k_fill8<<<64, 256, 0, s>>>(vm->page_marks, 2 * np, 0);
-        k_mark_pages_of<<<1, 64, 0, s>>>(d_row_ptr, src, vm->dev.page_shift - 2, vm->page_marks);
+        clear_page_list(vm, 0, s);
+        k_mark_pages_of<<<1, 64, 0, s>>>(d_row_ptr, src, vm->dev.page_shift - 2, page_list_of(vm, 0));
     }
     int levels = 0;
     for (int32_t cur = 0;; ++cur) {
         int changed = 0;
-        unsigned char *marks_cur = balanced ? vm->page_marks + (size_t)(cur & 1) * np : nullptr;
-        unsigned char *marks_next = balanced ? vm->page_marks + (size_t)((cur + 1) & 1) * np : nullptr;
+        const page_list_t work = balanced ? page_list_of(vm, cur & 1) : page_list_t{};
+        const page_list_t next = balanced ? page_list_of(vm, (cur + 1) & 1) : page_list_t{};
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
-        if (balanced) k_fill8<<<64, 256, 0, s>>>(marks_next, np, 0);
+        if (balanced) clear_page_list(vm, (cur + 1) & 1, s);
         if (direct)
             k_bfs_level_balanced<true><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv,
-                                                                                 marks_cur, marks_next, d_level, cur, vm->bfs_changed);
+                                                                                 work, next, d_level, cur, vm->bfs_changed);
         else if (balanced)
             k_bfs_level_balanced<false><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv,
-                                                                                  marks_cur, marks_next, d_level, cur, vm->bfs_changed);
+                                                                                  work, next, d_level, cur, vm->bfs_changed);
         else
             k_bfs_level<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, nv, d_level, cur, vm->bfs_changed);
         HIP_TRY(hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -344,7 +364,8 @@ int gpuvm_bench_bfs_zero_copy(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv,
 
 static int ensure_page_owner(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, hipStream_t s) {
     if (!vm->page_owner) HIP_TRY(hipMalloc(&vm->page_owner, ((size_t)vm->dev.n_pages + 1) * sizeof(unsigned int)));
-    if (!vm->page_marks) HIP_TRY(hipMalloc(&vm->page_marks, 2 * (size_t)vm->dev.n_pages));   // this round's and the next one's
+    // two page lists, this round's and the next one's: marks, list, count (padded)
+    if (!vm->page_marks) HIP_TRY(hipMalloc(&vm->page_marks, 2 * (2 * (size_t)vm->dev.n_pages + 64) * sizeof(unsigned int)));
     const unsigned int n = vm->dev.n_pages + 1;
     k_bfs_page_owner<<<(n + 255) / 256, 256, 0, s>>>(d_row_ptr, nv, vm->dev.n_pages, vm->dev.page_shift - 2, vm->page_owner);
     return GPUVM_OK;
@@ -392,9 +413,8 @@ int gpuvm_run_sssp_balanced(gpuvm_t *vm, gpuvm_t *vm_weights, const int64_t *d_r
     HIP_TRY(hipMalloc(&act, 2 * (size_t)nv));
     k_fill8<<<1024, 256, 0, s>>>(act, 2 * (size_t)nv, 0);
     k_fill8<<<1, 64, 0, s>>>(act + src, 1, 1);
-    const size_t np = vm->dev.n_pages;
-    k_fill8<<<64, 256, 0, s>>>(vm->page_marks, 2 * np, 0);
-    k_mark_pages_of<<<1, 64, 0, s>>>(d_row_ptr, src, vm->dev.page_shift - 2, vm->page_marks);
+    clear_page_list(vm, 0, s);
+    k_mark_pages_of<<<1, 64, 0, s>>>(d_row_ptr, src, vm->dev.page_shift - 2, page_list_of(vm, 0));
     k_fill32<<<1024, 256, 0, s>>>(d_dist, (size_t)nv, 0xFFFFFFFFu);
     k_fill32<<<1, 64, 0, s>>>(d_dist + src, 1, 0u);
     int rounds = 0;
@@ -402,13 +422,12 @@ int gpuvm_run_sssp_balanced(gpuvm_t *vm, gpuvm_t *vm_weights, const int64_t *d_r
     for (;;) {
         int changed = 0;
         unsigned char *cur = act + (size_t)(rounds & 1) * nv, *next = act + (size_t)((rounds + 1) & 1) * nv;
-        unsigned char *marks_cur = vm->page_marks + (size_t)(rounds & 1) * np;
-        unsigned char *marks_next = vm->page_marks + (size_t)((rounds + 1) & 1) * np;
+        const page_list_t work = page_list_of(vm, rounds & 1), work_next = page_list_of(vm, (rounds + 1) & 1);
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
         k_fill8<<<1024, 256, 0, s>>>(next, (size_t)nv, 0);
-        k_fill8<<<64, 256, 0, s>>>(marks_next, np, 0);
+        clear_page_list(vm, (rounds + 1) & 1, s);
         k_sssp_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, vm_weights->dev, d_row_ptr,
-                                                                        vm->page_owner, nv, marks_cur, marks_next, d_dist, cur, next,
+                                                                        vm->page_owner, nv, work, work_next, d_dist, cur, next,
                                                                         vm->bfs_changed);
         hipError_t e = hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);

@@ -410,7 +410,7 @@ __global__ __launch_bounds__(kBlock) void k_matvec_t(gpuvm_dev_t vm, unsigned lo
 // (one page each) below the pool size; beyond that every step would fault.
 // fp64 accumulation, columns ascending.
 template <int FLOATS> struct f32_chunk_t { float v[FLOATS]; };
-template <int FLOATS>     // floats per access: 16 (64 bytes in flight per lane and step) or 4
+template <int FLOATS>     // floats per access: 64 or 16 (256 or 64 bytes in flight per lane and step), or 4
 __global__ __launch_bounds__(kBlock) void k_matvec_rows(gpuvm_dev_t vm, unsigned long long rows, unsigned long long cols,
                                                          const float *__restrict__ x, double *__restrict__ y) {
     typedef f32_chunk_t<FLOATS> chunk_t;
@@ -699,7 +699,12 @@ int gpuvm_run_matvec(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x, do
     const int fit = (int)std::min<size_t>(vm->dev.n_frames * 3 / 4 / 64, 1 << 20) / kWavesPerBlock * kWavesPerBlock;
     const int waves = std::min(launch_waves(vm, (rows + 63) / 64), std::max(fit, kWavesPerBlock));
     if (waves < kWavesPerBlock) return GPUVM_EDEADLK;
-    if (cols % 16 == 0)
+    // the fewer waves the pool allows, the more each optimistic read has to carry: its three
+    // dependent loads are all that is in flight per lane (256 bytes per read: 46 ms instead of 78
+    // on a 1 GiB matrix with a pool of a twelfth, 16 waves; no difference when the link is the bound)
+    if (cols % 64 == 0 && waves < vm->cus * 2)
+        k_matvec_rows<64><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, d_x, d_y);
+    else if (cols % 16 == 0)
         k_matvec_rows<16><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, d_x, d_y);
     else
         k_matvec_rows<4><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, rows, cols, d_x, d_y);
