@@ -563,6 +563,24 @@ __device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned i
     return gpuvm_detail::acquire_page(vm, page_any, write, true);
 }
 
+/* gpuvm_acquire for callers that expect the page NOT to be resident (a scan, a
+ * fault-ahead, the first touch of a page per round): the page's word is read
+ * first, and if it says INVALID the reference and the INVALID -> LOADING lock are
+ * taken with one CAS on that value instead of an add followed by a CAS - one
+ * atomic less per fault; a resident page costs one more load than gpuvm_acquire.
+ * gpuvm_acquire_hinted takes the word from a caller that has read it already
+ * (the token of a gpuvm_peek that did not validate). */
+__device__ __forceinline__ char *gpuvm_acquire_hinted(const gpuvm_dev_t &vm, unsigned int page_any, bool write,
+                                                      unsigned long long word) {
+    return gpuvm_detail::acquire_page(vm, page_any, write, true, gpuvm_detail::bcast(word));
+}
+__device__ __forceinline__ char *gpuvm_acquire_cold(const gpuvm_dev_t &vm, unsigned int page_any, bool write) {
+    const unsigned int page = gpuvm_detail::bcast(page_any);
+    unsigned long long word = 0;
+    if (gpuvm_detail::wave_now().leader) word = gpuvm_detail::a_load(vm.pte + page);
+    return gpuvm_detail::acquire_page(vm, page, write, true, gpuvm_detail::bcast(word));
+}
+
 /* The same for a caller that will store every byte of the page before it
  * releases it: on a miss the frame is installed without reading the page from
  * the host (its old content would be overwritten anyway), which saves one page
@@ -587,7 +605,7 @@ __device__ __forceinline__ void gpuvm_release(const gpuvm_dev_t &vm, unsigned in
  * the data is not touched.  For waves that run ahead of the ones that will
  * use the page, the device-side counterpart of a prefetch hint. */
 __device__ __forceinline__ void gpuvm_touch(const gpuvm_dev_t &vm, unsigned int page_any) {
-    (void)gpuvm_acquire(vm, page_any, false);
+    (void)gpuvm_acquire_cold(vm, page_any, false);
     gpuvm_release(vm, page_any);
 }
 

@@ -155,8 +155,8 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
             const int len = end > beg ? (int)(end - beg) : 0;
             if (__builtin_amdgcn_ballot_w64(len > 0) == 0) continue;
             if (!ptr) {
-                ptr = in_place ? vm.host + ((size_t)page << vm.page_shift) : gpuvm_acquire(vm, page, false);
-                if (vm2) ptr2 = in_place ? vm2->host + ((size_t)page << vm2->page_shift) : gpuvm_acquire(*vm2, page, false);
+                ptr = in_place ? vm.host + ((size_t)page << vm.page_shift) : gpuvm_acquire_cold(vm, page, false);
+                if (vm2) ptr2 = in_place ? vm2->host + ((size_t)page << vm2->page_shift) : gpuvm_acquire_cold(*vm2, page, false);
             }
             auto edge_at = [&](unsigned int o) {
                 return in_place ? (int32_t)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(ptr, 1u << vm.page_shift), o, 0, GPUVM_AUX_SYSTEM)

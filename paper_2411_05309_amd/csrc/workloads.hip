@@ -185,7 +185,7 @@ __global__ __launch_bounds__(kBlock) void k_stream_reduce(gpuvm_dev_t vm, unsign
     for (unsigned int page = wave; page < vm.n_pages; page += nwaves) {
         const unsigned int len = page_len(vm, page);
         const unsigned int nvec = len >> 4;                           // float4 items
-        const char *p = gpuvm_acquire(vm, page, false);
+        const char *p = gpuvm_acquire_cold(vm, page, false);     // a scan: the page is rarely there already
         double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
         for (unsigned int i = lane; i < nvec; i += 64) {
             const u32x4 v = gpuvm_frame_load_b128(vm, p, i << 4);
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(kBlock) void k_embedding_bag(gpuvm_dev_t vm, const 
                             v[b] = load_row(vm.host + ((size_t)page[b] << vm.page_shift), o[b], from_host_t{});
                             gpuvm_wait_reads();
                         } else {
-                            const char *q = gpuvm_acquire(vm, page[b], false);
+                            const char *q = gpuvm_acquire_hinted(vm, page[b], false, again[b]);
                             v[b] = load_row(q, o[b], from_frame_t{});
                             gpuvm_release(vm, page[b]);
                         }
@@ -452,7 +452,7 @@ __global__ __launch_bounds__(kBlock) void k_filter_sum(gpuvm_dev_t vmk, gpuvm_de
     for (unsigned int page = wave; page < vmk.n_pages; page += nwaves) {
         const unsigned int n = page_len(vmk, page) >> 2;
         const unsigned long long first = (unsigned long long)page << elems_shift;
-        const char *p = gpuvm_acquire(vmk, page, false);
+        const char *p = gpuvm_acquire_cold(vmk, page, false);
         for (unsigned int i0 = 0; i0 < n; i0 += 64) {
             const unsigned int i = i0 + lane;
             const bool hit = i < n && gpuvm_frame_load_b32(vmk, p, i << 2) > threshold;
