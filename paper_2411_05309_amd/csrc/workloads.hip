@@ -145,7 +145,9 @@ __global__ __launch_bounds__(kBlock) void k_vector_add(gpuvm_dev_t a, gpuvm_dev_
     const size_t wave = ((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
     const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
     const size_t stripe = (size_t)1 << (c.page_shift - 2);               // floats per page of C
-    const gpuvm_array<float> A{a}, B{b}, C{c};
+    // the wave walks its stripe with a cursor per vector: the page it stands on stays
+    // pinned from one step to the next, so a step is three compares, two loads and a store
+    gpuvm_cursor_t ca = gpuvm_cursor_begin(), cb = gpuvm_cursor_begin(), cc = gpuvm_cursor_begin();
     for (size_t lo = wave * stripe; lo < n; lo += nwaves * stripe) {
         const size_t hi = lo + stripe < n ? lo + stripe : n;
         // OVERWRITE: the stripe is exactly one page of C and the wave stores all
@@ -157,15 +159,19 @@ __global__ __launch_bounds__(kBlock) void k_vector_add(gpuvm_dev_t a, gpuvm_dev_
         for (size_t i0 = lo; i0 < hi; i0 += 64) {
             const size_t i = i0 + lane;
             const bool want = i < hi;
+            const float x = gpuvm_cursor_load<float>(a, ca, want ? i : 0, want);
+            const float y = gpuvm_cursor_load<float>(b, cb, want ? i : 0, want);
             if (OVERWRITE) {
-                const float x = A.at(i, want), y = B.at(i, want);
                 if (want) gpuvm_frame_store_b32(c, fc, (unsigned int)(i - lo) * 4u, __float_as_uint(x + y));
             } else {
-                C.at(i, want) = (float)A.at(i, want) + (float)B.at(i, want);     // the listing's c[i] = a[i] + b[i]
+                gpuvm_cursor_store<float>(c, cc, want ? i : 0, x + y, want);         // the listing's c[i] = a[i] + b[i]
             }
         }
         if (OVERWRITE) gpuvm_release(c, page_c);
     }
+    gpuvm_cursor_end(a, ca);
+    gpuvm_cursor_end(b, cb);
+    if (!OVERWRITE) gpuvm_cursor_end(c, cc);
 }
 
 // Fault-ahead of a page range: wave w touches pages first + w, first + w + nwaves, ...
