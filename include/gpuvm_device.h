@@ -475,7 +475,11 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
     const unsigned long long flip =
         ((GPUVM_ST_LOADING ^ GPUVM_ST_RESIDENT) << GPUVM_PTE_STATE_SHIFT) |
         ((unsigned long long)f << GPUVM_PTE_FRAME_SHIFT) |
-        (vm.policy == GPUVM_POLICY_GCLOCK ? 0ull : GPUVM_PTE_REF) |        /* use count 0 there */
+        /* the reference bit of a new page: clear under the generalized CLOCK (use
+         * count 0), and clear when there is a front hand - that hand goes by this
+         * frame before the cursor comes back to it, so the bit set here could never
+         * decide anything and would only cost the front hand an atomic */
+        (vm.policy == GPUVM_POLICY_GCLOCK || gpuvm_clock_spread(vm) != 0 ? 0ull : GPUVM_PTE_REF) |
         (write ? GPUVM_PTE_DIRTY : 0ull) |
         ((unsigned long long)(gen ^ ((gen + 1u) & 0xFFFu)) << GPUVM_PTE_GEN_SHIFT);
     if (deferred) {
@@ -499,7 +503,8 @@ GPUVM_DEV unsigned int fault(const gpuvm_dev_t &vm, unsigned int page, bool writ
  * are tried as one CAS on it instead of an add followed by a CAS. */
 #define GPUVM_NO_HINT (~0ull)
 GPUVM_DEV char *acquire_page(const gpuvm_dev_t &vm, unsigned int page_any, bool write, bool fetch,
-                             unsigned long long hint = GPUVM_NO_HINT, unsigned long long *deferred = nullptr) {
+                             unsigned long long hint = GPUVM_NO_HINT, unsigned long long *deferred = nullptr,
+                             bool mark = true) {
     const wave_t w = wave_now();
     const unsigned int page = bcast(page_any);
     unsigned long long *pte = vm.pte + page;
@@ -543,7 +548,7 @@ GPUVM_DEV char *acquire_page(const gpuvm_dev_t &vm, unsigned int page_any, bool 
         if (w.leader) {
             unsigned long long need = 0;
             if (write && !(cur & GPUVM_PTE_DIRTY)) need |= GPUVM_PTE_DIRTY;
-            need |= gpuvm_use_mark(vm.policy, cur);
+            if (mark) need |= gpuvm_use_mark(vm.policy, cur);
             if (need) a_or(pte, need);
             if (vm.flags & GPUVM_F_ACCESS_STATS) stat_add(vm, GPUVM_S_HITS, 1);
         }
@@ -569,16 +574,21 @@ __device__ __forceinline__ char *gpuvm_acquire(const gpuvm_dev_t &vm, unsigned i
  * taken with one CAS on that value instead of an add followed by a CAS - one
  * atomic less per fault; a resident page costs one more load than gpuvm_acquire.
  * gpuvm_acquire_hinted takes the word from a caller that has read it already
- * (the token of a gpuvm_peek that did not validate). */
+ * (the token of a gpuvm_peek that did not validate).
+ * `last_use`: the caller will not come back to the page for a long time (one
+ * visit per page and round); a hit then leaves the replacement policy's mark
+ * as it is, so that the page is not kept in preference to pages that are still
+ * waiting for their visit. */
 __device__ __forceinline__ char *gpuvm_acquire_hinted(const gpuvm_dev_t &vm, unsigned int page_any, bool write,
                                                       unsigned long long word) {
     return gpuvm_detail::acquire_page(vm, page_any, write, true, gpuvm_detail::bcast(word));
 }
-__device__ __forceinline__ char *gpuvm_acquire_cold(const gpuvm_dev_t &vm, unsigned int page_any, bool write) {
+__device__ __forceinline__ char *gpuvm_acquire_cold(const gpuvm_dev_t &vm, unsigned int page_any, bool write,
+                                                    bool last_use = false) {
     const unsigned int page = gpuvm_detail::bcast(page_any);
     unsigned long long word = 0;
     if (gpuvm_detail::wave_now().leader) word = gpuvm_detail::a_load(vm.pte + page);
-    return gpuvm_detail::acquire_page(vm, page, write, true, gpuvm_detail::bcast(word));
+    return gpuvm_detail::acquire_page(vm, page, write, true, gpuvm_detail::bcast(word), nullptr, !last_use);
 }
 
 /* The same for a caller that will store every byte of the page before it
@@ -722,15 +732,27 @@ struct no_remote {};      /* tag: this access has no in-place form (writes, atom
 template <typename T, typename Op, typename Remote>
 GPUVM_DEV void access_missing(const gpuvm_dev_t &vm, unsigned int page, unsigned int off, bool write, bool pending,
                               unsigned long long word, Op op, Remote remote) {
+    /* The word of the page that comes after this one, read while this one's fault
+     * is under way: what the hit pass saw is a fault or more old by the time a
+     * later group's turn comes, and a stale word costs the lookup two atomics
+     * more (the CAS on it fails, an add and a second CAS follow). */
+    unsigned long long fresh = 0;
+    unsigned int fresh_page = GPUVM_NO_PAGE;
     for (;;) {
         const unsigned long long todo = __builtin_amdgcn_ballot_w64(pending);
         if (todo == 0) break;
         const unsigned int first = (unsigned int)__ffsll((long long)todo) - 1u;
         const unsigned int group_page = __builtin_amdgcn_readlane(page, first);
         /* what the group's first lane last saw in the page's word (the hit pass read it) */
-        const unsigned long long hint =
+        const unsigned long long hint = fresh_page == group_page ? bcast(fresh) :
             ((unsigned long long)(unsigned int)__builtin_amdgcn_readlane((unsigned int)(word >> 32), first) << 32) |
             (unsigned int)__builtin_amdgcn_readlane((unsigned int)word, first);
+        {
+            const unsigned long long later = __builtin_amdgcn_ballot_w64(pending && page != group_page);
+            fresh_page = later ? (unsigned int)__builtin_amdgcn_readlane(page, (unsigned int)__ffsll((long long)later) - 1u)
+                               : GPUVM_NO_PAGE;
+            if (later) fresh = a_load(vm.pte + fresh_page);           /* one address for the whole wave */
+        }
         if constexpr (!__is_same(Remote, no_remote)) {
             /* remote-first: the group's first lane asks whether the page has earned
              * its migration yet; if not, the lanes read host memory in place */

@@ -42,7 +42,7 @@ struct gpuvm {
     unsigned int phase_tag = 0;
     int *bfs_changed = nullptr;
     unsigned int *page_owner = nullptr;   // [n_pages + 1], edge-balanced BFS
-    unsigned int *page_marks = nullptr;   // two page lists (mark per page, list, count), edge-balanced BFS / SSSP: this round's and the next one's
+    unsigned int *page_marks = nullptr;   // two page lists (mark per page, list, taking order, counters), edge-balanced BFS / CC / SSSP: this round's and the next one's
     unsigned int *row_progress = nullptr; // [8192] row reached by each compute wave (column-order product)
 };
 

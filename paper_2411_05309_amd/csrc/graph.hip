@@ -97,22 +97,53 @@ __global__ void k_bfs_page_owner(const int64_t *__restrict__ row_ptr, int64_t nv
 struct page_list_t {
     unsigned int *mark;                            // [n_pages] 0 / 1
     unsigned int *list;                            // [n_pages] the marked pages
-    unsigned int *count;                           // [1] how many
+    unsigned int *order;                           // [n_pages] the round's pages that are not resident when it begins
+    unsigned int *ring;                            // [n_frames] those that are, by their frame's distance from the cursor
+    unsigned int *count;                           // [0] how many marked; [1] resident, [2] not; next to take: [3] of ring, [4] of order
 };
 __device__ __forceinline__ void mark_page(const page_list_t &next, unsigned int p) {
     if (next.mark[p] == 0 && atomicExch(next.mark + p, 1u) == 0) next.list[atomicAdd(next.count, 1u)] = p;
 }
 
-// `work` (may be null = every page): this round's page list.
+// A round's pages sorted for the waves: those that are not resident, in about
+// the order given (label propagation gains from ascending pages), and those that
+// the previous round left in the pool, each in the slot of its frame's distance
+// from the cursor - the order in which the allocator will come to evict them.
+// `every_page`: the round's pages are all pages (no list).  count[1..4] are
+// zero and ring[] is all GPUVM_NO_PAGE.
+__global__ __launch_bounds__(256) void k_sort_round(gpuvm_dev_t vm, page_list_t work, bool every_page) {
+    const unsigned int n = every_page ? vm.n_pages : *work.count;
+    const unsigned int cursor = (unsigned int)(a_load(vm.hand) % vm.n_frames);
+    for (unsigned int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
+        const unsigned int page = every_page ? i : work.list[i];
+        const unsigned long long w = a_load(vm.pte + page);
+        if (((w & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT) {
+            const unsigned int f = (unsigned int)(w >> GPUVM_PTE_FRAME_SHIFT);
+            if (f < vm.n_frames) {
+                work.ring[f >= cursor ? f - cursor : f + vm.n_frames - cursor] = page;
+                atomicAdd(work.count + 1, 1u);
+                continue;
+            }
+        }
+        work.order[atomicAdd(work.count + 2, 1u)] = page;
+    }
+}
+
+// `work`: this round's pages as k_sort_round left them.  The waves take them one
+// at a time from two shared counters: two resident pages for every page that has
+// to be faulted in, for as long as there are both.  The resident pages go in the
+// order in which the cursor will reach their frames and are let go without a
+// mark (gpuvm_acquire_cold, last_use), so the faults evict what has been used
+// already and stay behind the waves that use the rest: up to a pool's worth of
+// pages per round that do not cross the link again, used while the link is busy
+// with the others.
 template <bool DIRECT = false, class Active, class Visit>
 __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gpuvm_dev_t *vm2,
                                                  const int64_t *__restrict__ row_ptr,
                                                  const unsigned int *__restrict__ page_owner,
-                                                 const page_list_t *work,
+                                                 const page_list_t &work, bool every_page,
                                                  Active active, Visit visit) {
     const unsigned int lane = threadIdx.x & 63;
-    const unsigned int wave = (blockIdx.x * kBlock + threadIdx.x) >> 6;
-    const unsigned int nwaves = (gridDim.x * kBlock) >> 6;
     const unsigned int elems_shift = vm.page_shift - 2;
     const int64_t n_edges = (int64_t)(vm.bytes >> 2);
     constexpr int kSmall = 32;                    // lists up to this length: one lane each
@@ -120,9 +151,8 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
     // scale-26 BFS a factor of 2 was the fastest of 1, 1.5, 2, 3, 4, 8
     // (206, 146, 139, 142, 146, 157 ms; 197 ms with every page migrated)
     constexpr unsigned long long kInPlacePenalty = 2;
-    const unsigned int n_work = work ? *work->count : vm.n_pages;
-    for (unsigned int k = wave; k < n_work; k += nwaves) {
-        const unsigned int page = work ? work->list[k] : k;
+    const unsigned int n_miss = work.count[2];
+    auto do_page = [&](const unsigned int page) {
         const int64_t e_lo = (int64_t)page << elems_shift;
         const int64_t e_hi = min((long long)n_edges, (long long)(e_lo + ((int64_t)1 << elems_shift)));
         const int64_t v_first = page_owner[page], v_last = page_owner[page + 1];
@@ -155,8 +185,8 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
             const int len = end > beg ? (int)(end - beg) : 0;
             if (__builtin_amdgcn_ballot_w64(len > 0) == 0) continue;
             if (!ptr) {
-                ptr = in_place ? vm.host + ((size_t)page << vm.page_shift) : gpuvm_acquire_cold(vm, page, false);
-                if (vm2) ptr2 = in_place ? vm2->host + ((size_t)page << vm2->page_shift) : gpuvm_acquire_cold(*vm2, page, false);
+                ptr = in_place ? vm.host + ((size_t)page << vm.page_shift) : gpuvm_acquire_cold(vm, page, false, true);
+                if (vm2) ptr2 = in_place ? vm2->host + ((size_t)page << vm2->page_shift) : gpuvm_acquire_cold(*vm2, page, false, true);
             }
             auto edge_at = [&](unsigned int o) {
                 return in_place ? (int32_t)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(ptr, 1u << vm.page_shift), o, 0, GPUVM_AUX_SYSTEM)
@@ -190,6 +220,21 @@ __device__ __forceinline__ void walk_owned_pages(const gpuvm_dev_t &vm, const gp
             gpuvm_release(vm, page);
             if (vm2) gpuvm_release(*vm2, page);
         }
+    };
+    bool ring_left = !DIRECT && work.count[1] != 0, order_left = true;
+    for (unsigned int turn = 0; ring_left || order_left;) {
+        const bool from_ring = ring_left && (turn % 3 != 2 || !order_left);
+        unsigned int k = 0;
+        if (lane == 0) k = atomicAdd(work.count + (from_ring ? 3 : 4), 1u);
+        k = bcast(k);
+        if (k >= (from_ring ? vm.n_frames : n_miss)) {
+            if (from_ring) ring_left = false; else order_left = false;
+            continue;
+        }
+        const unsigned int page = from_ring ? work.ring[k] : work.order[k];
+        if (page == GPUVM_NO_PAGE) continue;          // a frame that holds none of this round's pages
+        do_page(page);
+        ++turn;
     }
 }
 
@@ -214,7 +259,7 @@ __global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, c
                                                                 int32_t *level, int32_t cur, int *changed) {
     int found = 0;
     const unsigned int elems_shift = vm.page_shift - 2;
-    walk_owned_pages<DIRECT>(vm, nullptr, row_ptr, page_owner, &work,
+    walk_owned_pages<DIRECT>(vm, nullptr, row_ptr, page_owner, work, false,
                      [&](int64_t v) { return level[v] == cur; },
                      [&](int64_t, int32_t u, unsigned int, const char *, bool) {
                          if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); return; }   // malformed neighbour id
@@ -232,9 +277,9 @@ __global__ __launch_bounds__(kBlock) void k_bfs_level_balanced(gpuvm_dev_t vm, c
 // labels each vertex with the smallest vertex id of its component.
 __global__ __launch_bounds__(kBlock) void k_cc_round_balanced(gpuvm_dev_t vm, const int64_t *__restrict__ row_ptr,
                                                                const unsigned int *__restrict__ page_owner, int64_t nv,
-                                                               int32_t *label, int *changed) {
+                                                               page_list_t work, int32_t *label, int *changed) {
     int found = 0;
-    walk_owned_pages(vm, nullptr, row_ptr, page_owner, nullptr,
+    walk_owned_pages(vm, nullptr, row_ptr, page_owner, work, true,
                      [&](int64_t) { return true; },
                      [&](int64_t v, int32_t u, unsigned int, const char *, bool) {
                          if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); return; }
@@ -262,7 +307,7 @@ __global__ __launch_bounds__(kBlock) void k_sssp_round_balanced(gpuvm_dev_t vm, 
                                                                  unsigned char *act_next, int *changed) {
     int found = 0;
     const unsigned int elems_shift = vm.page_shift - 2;
-    walk_owned_pages(vm, &vmw, row_ptr, page_owner, &work,
+    walk_owned_pages(vm, &vmw, row_ptr, page_owner, work, false,
                      [&](int64_t v) { return act_cur[v] != 0; },
                      [&](int64_t v, int32_t u, unsigned int off, const char *pw, bool in_place) {
                          if ((uint64_t)(uint32_t)u >= (uint64_t)nv) { raise_error(vm, GPUVM_ERANGE); return; }
@@ -289,8 +334,15 @@ __global__ void k_iota32(int32_t *p, size_t n) {
 // the two page lists of a handle (allocated by ensure_page_owner)
 static page_list_t page_list_of(const gpuvm_t *vm, int which) {
     const size_t np = vm->dev.n_pages;
-    unsigned int *base = vm->page_marks + (size_t)which * (2 * np + 64);
-    return page_list_t{base, base + np, base + 2 * np};
+    unsigned int *base = vm->page_marks + (size_t)which * (3 * np + vm->dev.n_frames + 64);
+    return page_list_t{base, base + np, base + 2 * np, base + 3 * np, base + 3 * np + vm->dev.n_frames};
+}
+// before a round's kernel: its pages in the order the waves take them
+static void order_pages(const gpuvm_t *vm, int which, bool every_page, hipStream_t s) {
+    const page_list_t l = page_list_of(vm, which);
+    k_fill32<<<1, 64, 0, s>>>(l.count + 1, 4, 0u);
+    k_fill32<<<64, 256, 0, s>>>(l.ring, vm->dev.n_frames, GPUVM_NO_PAGE);
+    k_sort_round<<<std::max(1u, std::min(256u, (vm->dev.n_pages + 255) / 256)), 256, 0, s>>>(vm->dev, l, every_page);
 }
 static void clear_page_list(const gpuvm_t *vm, int which, hipStream_t s) {
     const page_list_t l = page_list_of(vm, which);
@@ -327,7 +379,10 @@ static int run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t sr
         const page_list_t work = balanced ? page_list_of(vm, cur & 1) : page_list_t{};
         const page_list_t next = balanced ? page_list_of(vm, (cur + 1) & 1) : page_list_t{};
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
-        if (balanced) clear_page_list(vm, (cur + 1) & 1, s);
+        if (balanced) {
+            clear_page_list(vm, (cur + 1) & 1, s);
+            order_pages(vm, cur & 1, false, s);
+        }
         if (direct)
             k_bfs_level_balanced<true><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv,
                                                                                  work, next, d_level, cur, vm->bfs_changed);
@@ -364,8 +419,8 @@ int gpuvm_bench_bfs_zero_copy(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv,
 
 static int ensure_page_owner(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, hipStream_t s) {
     if (!vm->page_owner) HIP_TRY(hipMalloc(&vm->page_owner, ((size_t)vm->dev.n_pages + 1) * sizeof(unsigned int)));
-    // two page lists, this round's and the next one's: marks, list, count (padded)
-    if (!vm->page_marks) HIP_TRY(hipMalloc(&vm->page_marks, 2 * (2 * (size_t)vm->dev.n_pages + 64) * sizeof(unsigned int)));
+    // two page lists, this round's and the next one's: marks, list, order, ring, counters (padded)
+    if (!vm->page_marks) HIP_TRY(hipMalloc(&vm->page_marks, 2 * (3 * (size_t)vm->dev.n_pages + vm->dev.n_frames + 64) * sizeof(unsigned int)));
     const unsigned int n = vm->dev.n_pages + 1;
     k_bfs_page_owner<<<(n + 255) / 256, 256, 0, s>>>(d_row_ptr, nv, vm->dev.n_pages, vm->dev.page_shift - 2, vm->page_owner);
     return GPUVM_OK;
@@ -384,8 +439,9 @@ int gpuvm_run_cc_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int
     for (;;) {
         int changed = 0;
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
-        k_cc_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv, d_label,
-                                                                      vm->bfs_changed);
+        order_pages(vm, 0, true, s);
+        k_cc_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv,
+                                                                      page_list_of(vm, 0), d_label, vm->bfs_changed);
         HIP_TRY(hipMemcpyAsync(&changed, vm->bfs_changed, sizeof(int), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         ++rounds;
@@ -426,6 +482,7 @@ int gpuvm_run_sssp_balanced(gpuvm_t *vm, gpuvm_t *vm_weights, const int64_t *d_r
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
         k_fill8<<<1024, 256, 0, s>>>(next, (size_t)nv, 0);
         clear_page_list(vm, (rounds + 1) & 1, s);
+        order_pages(vm, rounds & 1, false, s);
         k_sssp_round_balanced<<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, vm_weights->dev, d_row_ptr,
                                                                         vm->page_owner, nv, work, work_next, d_dist, cur, next,
                                                                         vm->bfs_changed);

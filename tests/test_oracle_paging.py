@@ -190,14 +190,14 @@ def test_clock_keeps_a_reused_page_that_fifo_drops():
 
 # ---------------------------------------------------------------- two-handed CLOCK
 
-def two_hands_rotating_queue_model(refs, frames, spread):
+def two_hands_rotating_queue_model(refs, frames, spread, bit_on_load=1):
     """The two-handed clock told as a rotating queue: the ring of frames, seen
     from the cursor, is a queue whose head is the frame under the cursor (None =
     never used).  Each step of the cursor first lets the front hand clear the R
     bit of the element `spread` places behind the head of the queue, then looks
     at the head: an empty frame or a page with a clear bit gives way to the new
     page, which goes to the back; a page with its bit set loses the bit and goes
-    to the back itself.  R is set on load and on every use."""
+    to the back itself.  R is set on load (`bit_on_load`) and on every use."""
     q, rbit, faults, passes = deque([None] * frames), {}, 0, 0
     for p in refs:
         if p in rbit:
@@ -216,7 +216,7 @@ def two_hands_rotating_queue_model(refs, frames, spread):
             if head is not None:
                 del rbit[head]
             q.append(p)
-            rbit[p] = 1
+            rbit[p] = bit_on_load
             break
     return faults, {x for x in q if x is not None}, passes
 
@@ -251,6 +251,38 @@ def test_two_hands_long_skewed_traces_against_the_rotating_queue():
         assert set(own[own >= 0].tolist()) == resident
         differs += faults != second_chance_queue_model(refs, frames)[0]
     assert differs > 20                      # the second hand really changes the outcome
+
+
+def test_with_a_front_hand_the_bit_set_on_load_decides_nothing():
+    """A page enters at the back of the queue, F - 1 places behind the head; the
+    front hand, 1 <= S <= F - 1 places behind the head, clears its bit after
+    F - 1 - S steps, before the page can reach the head.  So whether a load sets
+    the bit or not changes no decision: same faults, same passes, same resident
+    set (the free-running fault path relies on this and leaves the bit clear,
+    which saves the front hand's atomic on pages that are never used again).
+    With one hand the bit on load does matter."""
+    checked = 0
+    for npages, frames, length in [(3, 2, 6), (4, 3, 7), (5, 4, 6)]:
+        for spread in range(1, frames):
+            for refs in itertools.product(range(npages), repeat=length):
+                assert (two_hands_rotating_queue_model(refs, frames, spread, bit_on_load=0)
+                        == two_hands_rotating_queue_model(refs, frames, spread, bit_on_load=1)), (refs, spread)
+                checked += 1
+    assert checked > 20000
+    rng = np.random.default_rng(23)
+    for _ in range(30):
+        npages = int(rng.integers(6, 80))
+        frames = int(rng.integers(2, npages))
+        spread = int(rng.integers(1, frames))
+        refs = np.minimum(rng.geometric(0.12, 3000) - 1, npages - 1).tolist()
+        faults, resident, passes = two_hands_rotating_queue_model(refs, frames, spread, bit_on_load=0)
+        sim = _run_pages(refs, frames, CLOCK, n_pages=npages, spread=spread)
+        assert sim.counters["faults"] == faults and sim.counters["sweeps"] == passes
+        own = sim.state()["owner"]
+        assert set(own[own >= 0].tolist()) == resident
+    refs = [1, 2, 3, 4, 2, 5, 2]
+    assert (two_hands_rotating_queue_model(refs, 3, 0, bit_on_load=0)
+            != two_hands_rotating_queue_model(refs, 3, 0, bit_on_load=1))
 
 
 def test_front_hand_on_the_cursor_is_the_one_handed_clock():
