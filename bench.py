@@ -65,6 +65,9 @@ def measure_link(gv, torch, np):
     for name, fn in (("wave_read_4k", lambda: gv.gpuvm_bench_read(h, nbytes, 4096, sink, 512)),
                      ("wave_read_64k", lambda: gv.gpuvm_bench_read(h, nbytes, 65536, sink, 512)),
                      ("wave_copy_4k", lambda: gv.gpuvm_bench_copy(d, h, nbytes, 4096, 512)),
+                     ("wave_copy_lds_staged_4k", lambda: gv.gpuvm_bench_copy_lds(d, h, nbytes, 4096, 512)),
+                     ("wave_copy_64k", lambda: gv.gpuvm_bench_copy(d, h, nbytes, 65536, 512)),
+                     ("wave_copy_lds_staged_64k", lambda: gv.gpuvm_bench_copy_lds(d, h, nbytes, 65536, 512)),
                      ("hipMemcpy_h2d", lambda: d.copy_(ht, non_blocking=True)),
                      ("wave_copy_d2h_64k", lambda: gv.gpuvm_bench_copy(h, d, nbytes, 65536, 512)),
                      ("hipMemcpy_d2h", lambda: ht.copy_(d, non_blocking=True))):
@@ -84,6 +87,12 @@ def measure_link(gv, torch, np):
     e0.record(); gv.gpuvm_bench_copy(d2, d, nbytes, 65536, 4096); e1.record()
     torch.cuda.synchronize()
     res["hbm_copy_rw"] = round(2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    e0, e1 = ev_pair(torch)
+    gv.gpuvm_bench_copy_lds(d2, d, nbytes, 65536, 4096)
+    torch.cuda.synchronize()
+    e0.record(); gv.gpuvm_bench_copy_lds(d2, d, nbytes, 65536, 4096); e1.record()
+    torch.cuda.synchronize()
+    res["hbm_copy_lds_staged_rw"] = round(2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
     # both directions at once (two streams of default priority): the ceiling for
     # a fault that writes a dirty victim back while other waves fetch.  256 waves
     # per direction is where two plain copies peak (48.5 GB/s each way; 45.5 with

@@ -455,6 +455,15 @@ GPUVM_API int gpuvm_run_scatter_increment_phased(gpuvm_t *vm, const uint32_t *d_
 GPUVM_API int gpuvm_bench_copy(void *dst, const void *src, size_t bytes,
                                size_t chunk_bytes, int waves, void *stream);
 
+/* The same copy with the data staged through LDS instead of registers (eight
+ * direct-to-LDS loads of 1 KiB per wavefront in flight, then LDS reads and
+ * stores): the other way to build the page mover, kept so that the two can be
+ * measured side by side (paper: Register usage - the runtime is inlined into
+ * every kernel, so what the mover holds in registers is every kernel's cost).
+ * bytes and chunk_bytes are multiples of 16; otherwise as gpuvm_bench_copy. */
+GPUVM_API int gpuvm_bench_copy_lds(void *dst, const void *src, size_t bytes,
+                                   size_t chunk_bytes, int waves, void *stream);
+
 /* Same traffic, reading only (every lane folds what it loaded into one word of
  * d_sink so the loads cannot be dropped): the read-side link / HBM ceiling. */
 GPUVM_API int gpuvm_bench_read(const void *src, size_t bytes, size_t chunk_bytes,

@@ -107,6 +107,7 @@ _SIGNATURES = {
     "gpuvm_run_gather_phased": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_run_scatter_increment_phased": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_void_p], C.c_int),
     "gpuvm_bench_copy": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p], C.c_int),
+    "gpuvm_bench_copy_lds": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p], C.c_int),
     "gpuvm_bench_read": ([C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p], C.c_int),
     "gpuvm_bench_latency": ([C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.c_void_p], C.c_int),
     "gpuvm_bench_scatter_plain": ([C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p], C.c_int),
@@ -366,6 +367,10 @@ def gpuvm_run_scatter_increment_phased(vm, d_idx, n, phase_len, stream=None):
 
 def gpuvm_bench_copy(dst, src, nbytes, chunk_bytes, waves=0, stream=None):
     _call("gpuvm_bench_copy", _ptr(dst), _ptr(src), nbytes, chunk_bytes, waves, _stream(stream))
+
+
+def gpuvm_bench_copy_lds(dst, src, nbytes, chunk_bytes, waves=0, stream=None):
+    _call("gpuvm_bench_copy_lds", _ptr(dst), _ptr(src), nbytes, chunk_bytes, waves, _stream(stream))
 
 
 def gpuvm_bench_read(src, nbytes, chunk_bytes, d_sink, waves=0, stream=None):

@@ -19,6 +19,45 @@ __global__ __launch_bounds__(kBlock) void k_bench_copy(char *dst, const char *sr
     }
 }
 
+// The same copy staged through LDS instead of registers: every wave owns 8 KiB
+// of LDS, fills it with eight direct-to-LDS loads (global_load_lds_dwordx4: lane
+// i's 16 bytes land at the slot's base + 16 i, no VGPR holds them), waits, and
+// writes the 8 KiB out with LDS reads and stores.  The alternative design of the
+// page mover, kept as a microbenchmark so that the choice between the two can
+// be measured.  `bytes` and `chunk` are multiples of 16.
+__global__ __launch_bounds__(kBlock) void k_bench_copy_lds(char *dst, const char *src, size_t bytes, size_t chunk) {
+    __shared__ __attribute__((aligned(16))) unsigned int stage[kWavesPerBlock][8][256];
+    const unsigned int lane = threadIdx.x & 63, wv = bcast(threadIdx.x >> 6);
+    const size_t wave = bcast((unsigned int)(((size_t)blockIdx.x * kBlock + threadIdx.x) >> 6));   // wave-uniform, in SGPRs
+    const size_t nwaves = ((size_t)gridDim.x * kBlock) >> 6;
+    const size_t nchunks = (bytes + chunk - 1) / chunk;
+    for (size_t c = wave; c < nchunks; c += nwaves) {
+        const size_t lo = c * chunk;
+        const size_t len = chunk < bytes - lo ? chunk : bytes - lo;
+        const __amdgpu_buffer_rsrc_t rd = make_rsrc(dst + lo, (unsigned int)len);
+        for (size_t o = 0; o < len; o += 8192) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const size_t at = o + (size_t)j * 1024 + lane * 16u;
+                if (at < len)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + lo + at),
+                                                     (__attribute__((address_space(3))) void *)&stage[wv][j][0], 16, 0,
+                                                     GPUVM_AUX_SYSTEM);
+            }
+            wait_vm();                                        // the loads have landed in LDS
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const size_t at = o + (size_t)j * 1024 + lane * 16u;
+                if (at < len) {
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(&stage[wv][j][lane * 4u]);
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rd, (unsigned int)at, 0, GPUVM_AUX_SYSTEM);
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // LDS read out before the next round overwrites it
+        }
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void k_bench_read(const char *src, size_t bytes, size_t chunk,
                                                         unsigned long long *sink) {
     const unsigned int lane = threadIdx.x & 63;
@@ -96,6 +135,14 @@ int gpuvm_bench_copy(void *dst, const void *src, size_t bytes, size_t chunk_byte
     if (!dst || !src || bytes == 0 || chunk_bytes < 16 || chunk_bytes % 16 || chunk_bytes > (1u << 30)) return GPUVM_EINVAL;
     k_bench_copy<<<grid_for_waves(bench_waves(waves)), kBlock, 0, (hipStream_t)stream>>>((char *)dst, (const char *)src,
                                                                                           bytes, chunk_bytes);
+    HIP_TRY(hipGetLastError());
+    return GPUVM_OK;
+}
+
+int gpuvm_bench_copy_lds(void *dst, const void *src, size_t bytes, size_t chunk_bytes, int waves, void *stream) {
+    if (!dst || !src || bytes == 0 || bytes % 16 || chunk_bytes < 16 || chunk_bytes % 16 || chunk_bytes > (1u << 30)) return GPUVM_EINVAL;
+    k_bench_copy_lds<<<grid_for_waves(bench_waves(waves)), kBlock, 0, (hipStream_t)stream>>>((char *)dst, (const char *)src,
+                                                                                              bytes, chunk_bytes);
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }

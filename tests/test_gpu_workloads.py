@@ -189,7 +189,8 @@ def test_store_then_load_roundtrip_through_eviction(gpu):
 
 # ---------------------------------------------------------------- CC and SSSP (edge-balanced)
 
-@pytest.mark.parametrize("scale,ef,page,frames", [(14, 16, 4096, 16), (16, 2, 65536, 8), (12, 1, 4096, 256)])
+@pytest.mark.parametrize("scale,ef,page,frames", [(14, 16, 4096, 16), (16, 2, 65536, 8), (12, 1, 4096, 256),
+                                                  (14, 16, 4096, 64), (16, 16, 4096, 1024)])
 def test_cc_balanced(gpu, scale, ef, page, frames):
     rp, ci = inputs.rmat_csr(7, scale, edge_factor=ef)
     nv = 1 << scale
@@ -202,6 +203,10 @@ def test_cc_balanced(gpu, scale, ef, page, frames):
         st, *_ = check_invariants(b, read_only=True, pristine=ci)
         if b.n_pages > frames:                                   # every round re-reads every page
             assert st["faults"] >= (rounds - 1) * (b.n_pages - frames)
+            if frames >= 64:
+                # ... and starts with what the round before left in the pool, before its own
+                # faults can evict it (a quarter of the pool at the very least)
+                assert st["faults"] <= rounds * b.n_pages - (rounds - 1) * (frames // 4)
 
 
 @pytest.mark.parametrize("scale,page,frames,src", [(14, 4096, 16, 0), (16, 65536, 8, 5), (12, 4096, 256, 0)])
@@ -432,3 +437,34 @@ def test_plain_scatter_microbenchmark_in_hbm_and_in_host_memory(gpu):
         assert np.array_equal(h, want)
     finally:
         gv.free_pinned(h)
+
+
+@pytest.mark.parametrize("nbytes,chunk,waves", [
+    ((1 << 20) + 4096 + 48, 4096, 64),       # last chunk 48 bytes
+    ((1 << 21) + 16, 65536, 16),             # eight 8 KiB rounds per chunk, last chunk 16 bytes
+    (5 * 20480 + 1040, 20480, 8),            # a chunk that is not a multiple of 8 KiB: two full rounds and half a one
+])
+def test_copy_microbenchmarks_move_every_byte(gpu, nbytes, chunk, waves):
+    """The two forms of the wavefront mover as microbenchmarks (staged through
+    registers, staged through LDS): host to device and back, byte for byte."""
+    src = inputs.u32_values(0x51, 0, (nbytes + 3) // 4).view(np.uint8)[:nbytes]
+    h = gv.pinned_array((nbytes,), np.uint8)
+    back = gv.pinned_array((nbytes,), np.uint8)
+    try:
+        for fn in (gv.gpuvm_bench_copy, gv.gpuvm_bench_copy_lds):
+            h[:] = src
+            back[:] = 0
+            d = torch.zeros(nbytes + 64, dtype=torch.uint8, device="cuda")     # 64 guard bytes behind the data
+            fn(d, h, nbytes, chunk, waves)
+            torch.cuda.synchronize()
+            got = d.cpu().numpy()
+            assert np.array_equal(got[:nbytes], src), fn.__name__
+            assert not got[nbytes:].any(), fn.__name__
+            fn(back, d, nbytes, chunk, waves)
+            torch.cuda.synchronize()
+            assert np.array_equal(back, src), fn.__name__
+        with pytest.raises(gv.GpuvmError):
+            gv.gpuvm_bench_copy_lds(d, h, nbytes - 8, chunk, waves)              # not a multiple of 16
+    finally:
+        gv.free_pinned(h)
+        gv.free_pinned(back)
