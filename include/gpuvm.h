@@ -178,8 +178,10 @@ GPUVM_API int gpuvm_configure(gpuvm_t *vm, uint32_t spin_limit, int access_stats
  * and with a whole wavefront as the mover and other wavefronts filling the
  * link in the meantime the gain is confined to launches with few wavefronts
  * in flight.  Left alone, the library's own launchers that dirty pages use the
- * overlapped order when they keep at most 128 wavefronts in flight and the
- * paper's order otherwise; a mode set here is used as it is. */
+ * overlapped order when they keep few wavefronts in flight (at most 64, or
+ * at most 256 on pages of 64 KiB and more: the counts up to which the link is
+ * not yet full) and the paper's order otherwise; a mode set here is used as it
+ * is. */
 enum { GPUVM_WB_SERIAL = 0, GPUVM_WB_OVERLAPPED = 1 };
 GPUVM_API int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode);
 
@@ -193,8 +195,10 @@ GPUVM_API int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode);
  * the paper) a front hand n_frames * spread_eighths / 8 positions (1..7 eighths
  * of the ring) ahead of the cursor clears the bit of the frame it stands on every time the cursor
  * advances; the cursor passes a frame only if its page was used again after
- * the front hand went by.  A new page is safe until the front hand reaches it,
- * a page that is not used again leaves at the cursor's first visit, and a scan
+ * the front hand went by.  A new page is safe until the cursor has gone once
+ * round (the bit it is installed with decides nothing: the front hand goes by
+ * before the cursor returns, so the free-running path leaves it clear), a
+ * page that is not used again leaves at the cursor's first visit, and a scan
  * makes the cursor pass nothing.  The larger the spread, the longer the time
  * in which a use still counts and the shorter a new page's protection.
  * Default: two hands half a ring apart (spread_eighths = 4).  Takes effect

@@ -89,13 +89,15 @@ int launch_waves_duplex(const gpuvm_t *vm, size_t work_waves) {
 
 // Unless the caller chose an order, a launch that dirties pages with few waves in
 // flight overlaps the write-back of a dirty victim with the fetch (one pass over
-// the frame, both directions in flight): measured, a fault is 15-18 % shorter
-// up to 64 waves on 4 KiB pages and 5-7 % up to 256 on 64 KiB pages, and no
-// shorter (1-3 % longer on 4 KiB pages) once the link is full, where the
-// paper's order - write back, then fetch - stays.
+// the frame, both directions in flight): measured, a run is about 10 % shorter
+// up to 64 waves on 4 KiB pages and 3-13 % from 32 to 256 waves on 64 KiB pages,
+// and no shorter (a few per cent longer on 4 KiB pages) once the link is full,
+// where the paper's order - write back, then fetch - stays.  The limit is the
+// wave count at which the link fills: 64 waves, 256 from 64 KiB pages on.
 gpuvm_dev_t dev_for_writers(const gpuvm_t *vm, int waves) {
     gpuvm_dev_t d = vm->dev;
-    if (!vm->wb_chosen && waves <= 128) d.flags |= GPUVM_F_OVERLAPPED_WRITEBACK;
+    const int limit = vm->page_bytes >= 65536 ? 256 : 64;
+    if (!vm->wb_chosen && waves <= limit) d.flags |= GPUVM_F_OVERLAPPED_WRITEBACK;
     return d;
 }
 

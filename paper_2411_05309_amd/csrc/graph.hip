@@ -109,15 +109,16 @@ __device__ __forceinline__ void mark_page(const page_list_t &next, unsigned int 
 // the order given (label propagation gains from ascending pages), and those that
 // the previous round left in the pool, each in the slot of its frame's distance
 // from the cursor - the order in which the allocator will come to evict them.
-// `every_page`: the round's pages are all pages (no list).  count[1..4] are
-// zero and ring[] is all GPUVM_NO_PAGE.
-__global__ __launch_bounds__(256) void k_sort_round(gpuvm_dev_t vm, page_list_t work, bool every_page) {
+// `every_page`: the round's pages are all pages (no list).  `in_place`: the round
+// reads host memory in place, whatever the pool holds.  count[1..4] are zero and
+// ring[] is all GPUVM_NO_PAGE.
+__global__ __launch_bounds__(256) void k_sort_round(gpuvm_dev_t vm, page_list_t work, bool every_page, bool in_place) {
     const unsigned int n = every_page ? vm.n_pages : *work.count;
     const unsigned int cursor = (unsigned int)(a_load(vm.hand) % vm.n_frames);
     for (unsigned int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
         const unsigned int page = every_page ? i : work.list[i];
         const unsigned long long w = a_load(vm.pte + page);
-        if (((w & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT) {
+        if (!in_place && ((w & GPUVM_PTE_STATE_MASK) >> GPUVM_PTE_STATE_SHIFT) == GPUVM_ST_RESIDENT) {
             const unsigned int f = (unsigned int)(w >> GPUVM_PTE_FRAME_SHIFT);
             if (f < vm.n_frames) {
                 work.ring[f >= cursor ? f - cursor : f + vm.n_frames - cursor] = page;
@@ -343,11 +344,11 @@ static page_list_t page_list_of(const gpuvm_t *vm, int which) {
     return page_list_t{base, base + np, base + 2 * np, base + 3 * np, base + 3 * np + vm->dev.n_frames};
 }
 // before a round's kernel: its pages in the order the waves take them
-static void order_pages(const gpuvm_t *vm, int which, bool every_page, hipStream_t s) {
+static void order_pages(const gpuvm_t *vm, int which, bool every_page, hipStream_t s, bool in_place = false) {
     const page_list_t l = page_list_of(vm, which);
     k_fill32<<<1, 64, 0, s>>>(l.count + 1, 4, 0u);
     k_fill32<<<64, 256, 0, s>>>(l.ring, vm->dev.n_frames, GPUVM_NO_PAGE);
-    k_sort_round<<<std::max(1u, std::min(256u, (vm->dev.n_pages + 255) / 256)), 256, 0, s>>>(vm->dev, l, every_page);
+    k_sort_round<<<std::max(1u, std::min(256u, (vm->dev.n_pages + 255) / 256)), 256, 0, s>>>(vm->dev, l, every_page, in_place);
 }
 static void clear_page_list(const gpuvm_t *vm, int which, hipStream_t s) {
     const page_list_t l = page_list_of(vm, which);
@@ -386,7 +387,7 @@ static int run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv, int64_t sr
         k_fill32<<<1, 64, 0, s>>>((unsigned int *)vm->bfs_changed, 1, 0u);
         if (balanced) {
             clear_page_list(vm, (cur + 1) & 1, s);
-            order_pages(vm, cur & 1, false, s);
+            order_pages(vm, cur & 1, false, s, direct);
         }
         if (direct)
             k_bfs_level_balanced<true><<<grid_for_waves(waves), kBlock, 0, s>>>(vm->dev, d_row_ptr, vm->page_owner, nv,

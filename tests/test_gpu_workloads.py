@@ -403,6 +403,15 @@ def test_bfs_zero_copy_baseline_matches_the_oracle(gpu):
         assert levels >= 2 and np.array_equal(host(d_level, np.int32), want)
         st = gv.gpuvm_stats(b.vm)
         assert st["faults"] == 0                                   # nothing was paged
+        # the same with pages in the pool (a paged run first): every page is still read in
+        # place, whatever is resident
+        gv.gpuvm_run_bfs_balanced(b.vm, dev(rp), 1 << 14, 0, d_level)
+        paged = gv.gpuvm_stats(b.vm)["faults"]
+        assert paged > 0
+        d_level.fill_(7)
+        gv.gpuvm_bench_bfs_zero_copy(b.vm, dev(rp), 1 << 14, 0, d_level)
+        assert np.array_equal(host(d_level, np.int32), want)
+        assert gv.gpuvm_stats(b.vm)["faults"] == paged
 
 
 @pytest.mark.parametrize("dim", [64, 128, 256])
