@@ -150,6 +150,16 @@ int main(int argc, char **argv) {
                         if (got < init_val[i] + lo || got > init_val[i] + hi) fail("validated peek out of bounds", i, got, init_val[i]);
                     }
                 }
+            } else if (x & 0x200) {                               // a one-visit page-level read: pinned, no reference mark
+                const unsigned page = (unsigned)((i * 8) >> shift);
+                const unsigned off = (unsigned)((i * 8) & (page_bytes - 1));
+                const u64 lo = completed[i].load();
+                const char *p = gpuvm_acquire_cold(vm, page, false, true);
+                const gpuvm_detail::u32x2 v = gpuvm_frame_load_b64(vm, p, off);
+                gpuvm_release(vm, page);
+                const u64 got = ((u64)v.y << 32) | v.x;
+                const u64 hi = announced[i].load();
+                if (hand[1] == 0 && (got < init_val[i] + lo || got > init_val[i] + hi)) fail("pinned page read out of bounds", i, got, init_val[i]);
             } else {                                              // fault-ahead
                 gpuvm_touch(vm, (unsigned)((i * 8) >> shift));
             }
