@@ -354,8 +354,14 @@ GPUVM_API int gpuvm_run_bfs(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv,
  * vertices (paper: Graph Workloads, Balanced CSR - an even number of faults
  * per worker, no serialisation behind huge neighbour lists): a wavefront owns
  * one page of col_idx per level and walks the segments of the frontier's
- * vertices inside it.  Same arguments and result as gpuvm_run_bfs; the
- * row_ptr array must be non-decreasing with row_ptr[nv] = bytes / 4. */
+ * vertices inside it.  A level visits only the pages that hold edges of its
+ * frontier, and starts with those of them that the level before left in the
+ * pool (paper: Multi-kernel support - mappings persist from kernel to
+ * kernel): the resident pages are taken in the order in which the allocator
+ * would evict them, two for every page that has to be faulted in.  Same
+ * arguments and result as gpuvm_run_bfs; the row_ptr array must be
+ * non-decreasing with row_ptr[nv] = bytes / 4.  The CC and SSSP launchers
+ * below walk their rounds the same way. */
 GPUVM_API int gpuvm_run_bfs_balanced(gpuvm_t *vm, const int64_t *d_row_ptr, int64_t nv,
                                      int64_t src, int32_t *d_level, int *n_levels_out,
                                      void *stream);
