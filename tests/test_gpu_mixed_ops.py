@@ -23,6 +23,7 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("n64,page,frames,seed", [
     ((1 << 16) + 37, 4096, 24, 1),       # 129 pages (the last one short) over 24 frames
     (1 << 17, 65536, 8, 2),              # 16 pages of 64 KiB over the smallest pool
+    ((1 << 18) + 5, 4096, 256, 3),       # 513 pages over 256 frames: 128 waves, every wave with many pages per access
 ])
 def test_random_operation_sequence_matches_the_model(gpu, policy, wb_mode, remote_bytes, n64, page, frames, seed):
     model = inputs.u32_values(seed, 0, 2 * n64).view(np.uint64).copy()      # arbitrary initial content

@@ -228,6 +228,23 @@ def test_sssp_balanced(gpu, scale, page, frames, src):
             gv.gpuvm_run_sssp_balanced(b.vm, b.vm, dev(rp), nv, src, d_dist)
 
 
+def test_sssp_pools_of_different_size(gpu):
+    """The two paged arrays of SSSP need not have pools of the same size: a round's
+    pages are ordered by what the pool of col_idx holds, the weights follow."""
+    rp, ci = inputs.rmat_csr(9, 14)
+    w = inputs.edge_weights(4, 0, ci.size)
+    nv = 1 << 14
+    want = oracle.sssp(rp, ci, w, 3)
+    with Backing(ci, 4096, 64 * 4096) as b, Backing(w, 4096, 24 * 4096) as bw:
+        d_dist = torch.zeros(nv, dtype=torch.int32, device="cuda")
+        rounds = gv.gpuvm_run_sssp_balanced(b.vm, bw.vm, dev(rp), nv, 3, d_dist)
+        assert rounds >= 2
+        assert np.array_equal(host(d_dist, np.uint32), want)
+        st, *_ = check_invariants(b, read_only=True, pristine=ci)
+        stw, *_ = check_invariants(bw, read_only=True, pristine=w)
+        assert stw["faults"] >= st["faults"]                       # the smaller pool keeps less from round to round
+
+
 # ---------------------------------------------------------------- column-order access, sparse filter
 
 @pytest.mark.parametrize("rows,cols,page,frames", [
