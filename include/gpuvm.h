@@ -252,7 +252,10 @@ GPUVM_API int gpuvm_max_waves_duplex(const gpuvm_t *vm);
 /* The same for the launchers that are plain streams of page faults with little
  * work per page (gpuvm_run_stream_reduce, _embedding_bag, _prefetch): on a pool
  * smaller than the data set they keep about 4 MiB of page traffic in flight,
- * which fills the link; more only queues in front of the other memory traffic. */
+ * which fills the link; more only queues in front of the other memory traffic.
+ * On a pool that holds every page - hits only, after the first touch - they
+ * run 16 wavefronts per compute unit, where reads of resident pages come
+ * closest to a plain read of HBM. */
 GPUVM_API int gpuvm_max_waves_streaming(const gpuvm_t *vm);
 
 /* Write every DIRTY page back to host_buf and clear the dirty bits; pages stay

@@ -64,11 +64,18 @@ int launch_waves(const gpuvm_t *vm, size_t work_waves) {
 // pages (a wave has 8 KiB outstanding) against 55.5 with 2048, the embedding
 // configuration 12.3 s against 12.75.  Kernels that also compute between their
 // faults (the graph walks) or serve hits lane by lane (the gather) keep the full
-// count; so does a pool that holds the whole data set, where only the first touch
-// of a page faults.  A wave count chosen by the caller stands.
+// count.  A wave count chosen by the caller stands.
 int launch_waves_streaming(const gpuvm_t *vm, size_t work_waves) {
     const int all = launch_waves(vm, work_waves);
-    if (vm->waves_chosen || vm->dev.n_frames >= vm->dev.n_pages) return all;
+    if (vm->waves_chosen) return all;
+    if (vm->dev.n_frames >= vm->dev.n_pages) {
+        // every page fits: hits after the first touch, bound by the latency of HBM and
+        // of the one pin per page - 16 waves per CU read resident 64 KiB pages at 5.3 TB/s
+        // (a plain read of the same bytes: 5.7), 8 at 3.5, 32 at 4.9
+        const long long cap = (long long)vm->cus * 16;
+        const long long need = (long long)((std::max<size_t>(work_waves, 1) + kWavesPerBlock - 1) / kWavesPerBlock) * kWavesPerBlock;
+        return (int)std::min(cap, need);
+    }
     const size_t per_wave = std::min<size_t>(vm->page_bytes, 8192);
     const int sweet = (int)((4u << 20) / per_wave) / kWavesPerBlock * kWavesPerBlock;
     return std::max(std::min(all, sweet), std::min(all, kWavesPerBlock));

@@ -42,3 +42,7 @@ def test_default_bench_line(gpu):
     dd = d["dedup"]                                                      # wavefront dedup and arbitration, in numbers
     assert dd["wave_page_groups"] + dd["lanes_coalesced"] == dd["lane_accesses"] == d["config"]["indices"]
     assert dd["hits"] + dd["faults"] == dd["wave_page_groups"] and dd["lanes_per_group"] >= 1.0
+    hp = d["hit_path"]                                                   # hits only, each leg with a roofline object of its own
+    for leg in ("random_4KiB_pages", "random_64KiB_pages", "unit_stride_4KiB_pages", "unit_stride_64KiB_pages", "whole_pages_64KiB"):
+        assert hp[leg]["parity"] and hp[leg]["new_faults"] == 0, leg
+        assert hp[leg]["roofline"]["bound"] == "hbm" and 0 < hp[leg]["roofline"]["frac"] <= 1.0, leg
