@@ -196,10 +196,8 @@ GPUVM_API int gpuvm_set_writeback_mode(gpuvm_t *vm, int mode);
  * of the ring) ahead of the cursor clears the bit of the frame it stands on every time the cursor
  * advances; the cursor passes a frame only if its page was used again after
  * the front hand went by.  A new page is safe until the cursor has gone once
- * round (the bit it is installed with decides nothing: the front hand goes by
- * before the cursor returns, so the free-running path leaves it clear), a
- * page that is not used again leaves at the cursor's first visit, and a scan
- * makes the cursor pass nothing.  The larger the spread, the longer the time
+ * round, a page that is not used again leaves at the cursor's first visit,
+ * and a scan makes the cursor pass nothing.  The larger the spread, the longer the time
  * in which a use still counts and the shorter a new page's protection.
  * Default: two hands half a ring apart (spread_eighths = 4).  Takes effect
  * with the next launch. */

@@ -645,7 +645,7 @@ static int run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x,
     const unsigned int skew = (unsigned int)std::max<size_t>(1, std::min<size_t>({(size_t)64, rows_in_pool / 4, rows}));
     // one pass over the rows per wave is what the window reasons about
     const bool single_pass = (size_t)waves * 64 >= cols;
-    // Under the two-handed CLOCK a page keeps its first reference bit for the part of
+    // Under the two-handed CLOCK a page keeps the reference bit it is installed with for the part of
     // the ring the front hand has not covered yet, (8 - e) / 8 of it; a page that is
     // still being used after that is marked again and outlives its turn by a whole
     // lap, dead weight that the rows in flight then lack.  So every use of a page -

@@ -258,9 +258,7 @@ def test_with_a_front_hand_the_bit_set_on_load_decides_nothing():
     front hand, 1 <= S <= F - 1 places behind the head, clears its bit after
     F - 1 - S steps, before the page can reach the head.  So whether a load sets
     the bit or not changes no decision: same faults, same passes, same resident
-    set (the free-running fault path relies on this and leaves the bit clear,
-    which saves the front hand's atomic on pages that are never used again).
-    With one hand the bit on load does matter."""
+    set.  With one hand the bit on load does matter."""
     checked = 0
     for npages, frames, length in [(3, 2, 6), (4, 3, 7), (5, 4, 6)]:
         for spread in range(1, frames):
