@@ -655,7 +655,13 @@ static int run_matvec_t(gpuvm_t *vm, size_t rows, size_t cols, const float *d_x,
     // generalized CLOCK keep half the pool.
     const unsigned int eighths = (vm->dev.flags >> GPUVM_F_HANDS_SHIFT) & GPUVM_F_HANDS_MASK;
     const bool two_hands = eighths && (vm->dev.policy == GPUVM_POLICY_CLOCK || vm->dev.policy == GPUVM_POLICY_CLOCK_WRITE_AWARE);
-    const size_t lead = two_hands ? rows_in_pool * (8 - eighths) / 16 : rows_in_pool / 2;
+    // ... and no further ahead than 64 MiB of rows: the link is full with a few MiB in
+    // flight, and a longer lead only spreads the compute waves over more pages at a
+    // time (a pool that holds everything: 28.1 -> 22.6 ms on 16384 x 16384, 86.6 ->
+    // 75.6 ms on 32768 x 32768; a quarter of that: 77.8 -> 76.7 ms; 16 MiB is too
+    // short for two-page rows, 81.7 ms)
+    const size_t lead = std::min<size_t>(two_hands ? rows_in_pool * (8 - eighths) / 16 : rows_in_pool / 2,
+                                         std::max<size_t>(16, ((size_t)64 << 20) / (cols * 4)));
     const unsigned int window = single_pass && rows_in_pool >= 16 ? (unsigned int)std::min<size_t>(std::max<size_t>(lead, 4), 0x7FFFFFFF) : 0;
     // fault-ahead helpers: what is left of the wave budget, at most two per compute unit
     const int helpers = window ? std::min(cap - waves, vm->cus * 2) / kWavesPerBlock * kWavesPerBlock : 0;
