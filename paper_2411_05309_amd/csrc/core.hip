@@ -155,7 +155,7 @@ table_layout layout_for(size_t bytes, size_t page_bytes, size_t frame_pool_bytes
     l.pte = up(n_frames * page_bytes);
     l.owner = l.pte + up(n_pages * sizeof(unsigned long long));
     l.hand = l.owner + up(n_frames * sizeof(unsigned int));
-    l.stats = l.hand + up(2 * sizeof(unsigned long long));
+    l.stats = l.hand + up(4 * sizeof(unsigned long long));
     l.flag = l.stats + up((size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT * sizeof(unsigned long long));
     l.total = l.flag + up(sizeof(int));
     return l;
@@ -255,14 +255,14 @@ static int create_view(void *host_buf, size_t bytes, size_t page_bytes, size_t f
         alloc((void **)&d.frames, n_frames * page_bytes);
         alloc((void **)&d.pte, n_pages * sizeof(unsigned long long));
         alloc((void **)&d.frame_owner, n_frames * sizeof(unsigned int));
-        alloc((void **)&d.hand, 2 * sizeof(unsigned long long));
+        alloc((void **)&d.hand, 4 * sizeof(unsigned long long));
         alloc((void **)&d.stats, (size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT * sizeof(unsigned long long));
         alloc((void **)&vm->bfs_changed, sizeof(int));
     }
     if (rc) { gpuvm_destroy(vm); return rc; }
     k_fill64<<<256, 256>>>(d.pte, n_pages, 0ull);
     k_fill32<<<256, 256>>>(d.frame_owner, n_frames, GPUVM_NO_PAGE);
-    k_fill64<<<1, 64>>>(d.hand, 2, 0ull);
+    k_fill64<<<1, 64>>>(d.hand, 4, 0ull);
     k_fill64<<<4, 256>>>(d.stats, (size_t)GPUVM_STAT_SLOTS * GPUVM_S_COUNT, 0ull);
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); gpuvm_destroy(vm); return GPUVM_EHIP; }
     *out = vm;

@@ -33,14 +33,25 @@ __global__ __launch_bounds__(kBlock) void k_gather(gpuvm_dev_t vm, const uint32_
     const size_t lo = wave * per_wave, hi = lo + per_wave < n ? lo + per_wave : n;
     unsigned long long acc = 0;
     if constexpr (PER_LANE == 1) {
+        // the waves take runs of 256 indices from a shared counter (hand[2], zero at
+        // launch): how many of a wave's indices miss is a matter of chance, and with
+        // fixed shares the waves that drew the most misses finish alone, the link idle
         gpuvm_cursor_t cur = gpuvm_cursor_begin();
-        for (size_t k0 = lo; k0 < hi; k0 += 64) {
-            const size_t k = k0 + lane;
-            unsigned long long i = k < hi ? idx[k] : 0;
-            bool want = k < hi;
-            if (want && i >= n_elems) { raise_error(vm, GPUVM_ERANGE); want = false; }
-            const uint32_t v = gpuvm_cursor_load<uint32_t>(vm, cur, i, want);
-            if (want) { out[k] = v; acc += v; }
+        constexpr size_t kRun = 256;
+        for (;;) {
+            unsigned int r = 0;
+            if (lane == 0) r = (unsigned int)__hip_atomic_fetch_add(vm.hand + 2, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const size_t run_lo = (size_t)bcast(r) * kRun;
+            if (run_lo >= n) break;
+            const size_t run_hi = run_lo + kRun < n ? run_lo + kRun : n;
+            for (size_t k0 = run_lo; k0 < run_hi; k0 += 64) {
+                const size_t k = k0 + lane;
+                unsigned long long i = k < run_hi ? idx[k] : 0;
+                bool want = k < run_hi;
+                if (want && i >= n_elems) { raise_error(vm, GPUVM_ERANGE); want = false; }
+                const uint32_t v = gpuvm_cursor_load<uint32_t>(vm, cur, i, want);
+                if (want) { out[k] = v; acc += v; }
+            }
         }
         gpuvm_cursor_end(vm, cur);
     } else {
@@ -499,9 +510,11 @@ int gpuvm_run_gather(gpuvm_t *vm, const uint32_t *d_idx, size_t n, uint32_t *d_o
     if (all_fit && n >= (size_t)waves * 256)
         k_gather<4><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, d_out,
                                                                                 (unsigned long long *)d_sum, vm->dev.bytes / 4);
-    else
+    else {
+        k_fill64<<<1, 64, 0, (hipStream_t)stream>>>(vm->dev.hand + 2, 1, 0ull);     // the runs' counter (a fill kernel: capturable)
         k_gather<1><<<grid_for_waves(waves), kBlock, 0, (hipStream_t)stream>>>(vm->dev, d_idx, n, d_out,
                                                                                 (unsigned long long *)d_sum, vm->dev.bytes / 4);
+    }
     HIP_TRY(hipGetLastError());
     return GPUVM_OK;
 }
