@@ -48,6 +48,9 @@
  * before first use).  hand[0] is the global head cursor of the frame ring;
  * ticket t names frame t mod n_frames (paper: Eviction scheme - the leader
  * atomically takes the next mapping and may not choose a frame).
+ * hand[1] holds the first error a kernel recorded; hand[2] is a work counter
+ * of the library's own launchers (zero at launch) and of no concern to
+ * kernels written against this header.
  *
  * Coherence and ordering.  Each XCD of the MI355X has its own L2, and the
  * L1/L2 are not kept coherent with each other by hardware for ordinary loads
